@@ -55,10 +55,11 @@ typedef enum {
     MOE_ERR_NULL = 1,        /* a required pointer is NULL                                   */
     MOE_ERR_SHAPE = 2,       /* inconsistent sizes (k > E, T > max_tokens, T != T_in, ...)   */
     MOE_ERR_ALIGN = 3,       /* a base pointer is not 16-byte aligned (ws: 256-byte)         */
-    MOE_ERR_WORKSPACE = 4,   /* no room: the expert cache cannot place a demanded expert     */
+    MOE_ERR_WORKSPACE = 4,   /* the scratch memory at hand is too small for this config      */
     MOE_ERR_UNSUPPORTED = 5, /* valid layer, but outside the shapes this build supports      */
     MOE_ERR_HIP = 6,         /* a kernel launch failed                                       */
-    MOE_ERR_INDEX = 7        /* index checking is on and an index array holds an entry out of range */
+    MOE_ERR_INDEX = 7,       /* index checking is on and an index array holds an entry out of range */
+    MOE_ERR_CACHE_FULL = 8   /* the expert cache cannot place a demanded expert: nothing is evictable */
 } moe_status;
 
 typedef struct {
@@ -98,8 +99,8 @@ moe_status moe_expert_ffn(const moe_config* cfg, const moe_bf16* x, int32_t T_in
                           const int32_t* expert_offsets, const int32_t* sorted_token, const moe_bf16* w_gate,
                           const moe_bf16* w_up, const moe_bf16* w_down, moe_bf16* y_sorted, void* ws, void* stream);
 
-/* Routed experts whose weights are addressed through a slab table (paper Sec. 3.4.2: the dynamic expert cache is
- * pre-partitioned into fixed-size slabs, each storing one expert, so nothing is allocated at run time). Same
+/* Routed experts whose weights are addressed through a slab table (paper Sec. 3.4.2: the expert cache hands out
+ * equal-sized slots, one expert per slot, carved once from a single region, so nothing is allocated at run time). Same
  * operation as moe_expert_ffn, except that expert e's weights are read from slab_table[e]:
  *   slab_table [E]  DEVICE array of DEVICE pointers (16-byte aligned each); NULL = expert e is not resident.
  *                   A slab is [ w_gate_e (I x H) | w_up_e (I x H) | w_down_e (H x I) ] bf16, contiguous.
@@ -136,8 +137,10 @@ moe_status moe_layer_forward(const moe_config* cfg, const moe_bf16* x, int32_t T
                              void* ws, void* stream);
 
 /* Stage timing, a measurement aid for benchmarks (not part of the layer; no passage of the paper defines it).
- * While enabled, every call brackets each of its stages with a pair of HIP events recorded on the call's stream:
- *   stage 0 route, 1 dispatch, 2 grouped gate/up + SwiGLU, 3 grouped down, 4 combine.
+ * While enabled, every call of the layer (the fused one and the per-step ones) brackets each stage it runs with a
+ * pair of HIP events recorded on the call's stream:
+ *   stage 0 route, 1 dispatch, 2 grouped gate/up + SwiGLU, 3 grouped down, 4 combine (for moe_shared_ffn: the sum
+ *   over the shared experts).
  * moe_stage_timing_enable(1) creates the events (this one call allocates); (0) destroys them.
  * moe_stage_timing_read waits for the LAST call's events and writes the elapsed milliseconds of each stage to
  * ms_out (HOST pointer, MOE_N_STAGES floats; stages the last call did not run read 0). Timing state is
@@ -160,16 +163,14 @@ moe_status moe_index_checks_enable(int32_t enable);
 
 /* ---- Affinity-aware token compression (paper Sec. 3.2, Alg. 1, Eq. 1-5): the producer of keep_idx.
  *
- *   s        = mean over heads of attn[h, :]                       (head-averaged saliency of the N visual tokens)
- *   s~       = (s - min s) / (max s - min s), 0 when all equal     (Normalize to [0, 1])
- *   K_core   = floor(alpha N), K_keep = floor(beta N)              (on the double-precision products)
- *   I_core   = the K_core tokens of largest s~                     (Eq. 1; ties to the lower token index)
- *   E_i      = union over the L prefix layers of prefix_topk_ids[l, i, :]   (ActiveExperts(R_i); ids outside
- *                                                                   [0, E) are ignored)
- *   E_target = union of E_j over I_core
- *   Delta_i  = |E_i \ E_target| / |E_i|, 0 when E_i is empty       (Eq. 2 / Eq. 3)
- *   p_i      = s~_i - lambda Delta_i for i outside I_core           (Eq. 4)
- *   I_keep   = I_core  u  the K_keep - K_core outside tokens of largest p  (Eq. 5; ties to the lower index)
+ * Data flow: (1) the saliency of each of the N visual tokens is the attention it receives, averaged over the heads
+ * and rescaled min-max to [0, 1] (all-equal saliency rescales to 0); (2) the floor(alpha N) most salient tokens form
+ * the core and are always kept; (3) each token carries the set of experts it was routed to in the L pinned-prefix
+ * layers, as an E-bit mask (ids outside [0, E) are ignored), and the core's masks are OR-ed into one target mask;
+ * (4) a token's novelty is the share of its own experts that are missing from the target mask (0 for an empty
+ * mask); (5) tokens outside the core score saliency - lambda * novelty; (6) the floor(beta N) - floor(alpha N)
+ * best-scoring of them are kept as well. Every selection takes the largest values with ties to the lower token
+ * index; both floors are taken on the double-precision products.
  *
  * All score arithmetic is fp32 with one rounding per operation and the head sum in head order, so the selection
  * is reproducible bit for bit on a CPU.
@@ -177,7 +178,8 @@ moe_status moe_index_checks_enable(int32_t enable);
  *   prefix_topk_ids [L, N, k] int32     top-k ids of each visual token in the L pinned-prefix layers (moe_route's
  *                                       topk_ids of those layers, stacked)
  *   -> keep_idx [floor(beta N)] int32, ascending token indices (positions in the visual-token array)
- *   -> s_norm_opt [N] float (s~) and delta_opt [N] float (Delta_i; 0 for core tokens): optional, NULL to skip
+ *   -> s_norm_opt [N] float (rescaled saliency) and delta_opt [N] float (novelty; 0 for core tokens): optional,
+ *      NULL to skip
  * `ws` needs moe_compress_workspace_bytes(N, E) bytes, 256-byte aligned. Limits: 1 <= E <= 512, n_heads >= 1,
  * L >= 1, k >= 1, 0 <= alpha <= beta <= 1, N <= 2^22; otherwise MOE_ERR_SHAPE / MOE_ERR_UNSUPPORTED. N == 0 or
  * K_keep == 0 returns MOE_OK without launching (no output is written, the optional ones included). Inputs must be finite. The other conventions (device
@@ -223,10 +225,10 @@ moe_status moe_routing_histogram(const int32_t* ids, int64_t n, int32_t E, float
 moe_status moe_lookahead_target(const int32_t* future_ids, int32_t W, int64_t n, int32_t E, float gamma, float* g,
                                 void* stream);
 
-/* ---- Slab-based dynamic expert cache with a transfer and a compute stream (paper Sec. 3.4.2: the cache region is
- * pre-partitioned into fixed-size slabs, each storing one expert; lookahead-driven insertion; safety-guarded
- * eviction of Required / Speculative / Expired experts. Sec. 3.4.3: transfers run on their own stream, and a miss
- * stalls the compute stream only on the expert concerned).
+/* ---- Slab-based dynamic expert cache with a transfer and a compute stream (paper Sec. 3.4.2: equal-sized slots,
+ * one expert each, carved once from the cache region; insertion driven by the lookahead predictions; eviction
+ * guarded by the classes Required / Speculative / Expired. Sec. 3.4.3: transfers run on their own stream, and a
+ * miss stalls the compute stream only on the expert concerned).
  *
  * Host-side object; it allocates no device memory (the caller hands over the pool) and launches no kernels: it
  * issues host-to-device copies on the transfer stream and event waits. An expert is (layer, expert), 0 <= layer <
@@ -247,7 +249,11 @@ moe_status moe_lookahead_target(const int32_t* future_ids, int32_t W, int64_t n,
  *                    the others are fetched on demand (ascending expert, priority 0). Writes the layer's slab
  *                    table (HOST array of E device pointers, NULL for experts not needed: copy it to the device
  *                    and pass it to moe_expert_ffn_slabs) and makes comp_stream wait for exactly those experts'
- *                    copies. MOE_ERR_WORKSPACE when a demanded expert cannot be placed (nothing is Expired).
+ *                    copies. MOE_ERR_CACHE_FULL when a demanded expert cannot be placed (nothing is Expired):
+ *                    the misses placed before it stay resident as Required with their copies in flight
+ *                    (missed_out / n_missed list them), the hits stay Required, no table is written and
+ *                    comp_stream waits for nothing; the caller retries after a moe_cache_layer_done has made
+ *                    experts evictable, or gives the cache more slabs.
  *                    -> missed_out [n] (optional), n_missed.
  * moe_cache_layer_done  after the layer's kernels are enqueued on comp_stream: its experts become Expired; a copy
  *                    that later reuses one of their slabs first waits for this point of comp_stream.

@@ -130,8 +130,8 @@ def expert_ffn(xt: np.ndarray, expert_offsets: np.ndarray, sorted_token: np.ndar
 
 def expert_ffn_slabs(xt: np.ndarray, expert_offsets: np.ndarray, sorted_token: np.ndarray, slabs, I: int,
                      dtype=np.float32):
-    """Step 6 with the weights addressed through a per-expert slab table (paper Sec. 3.4.2: the dynamic expert cache is
-    pre-partitioned into fixed-size slabs, each storing one expert). slabs[e] is None when expert e is not resident,
+    """Step 6 with the weights addressed through a per-expert slab table (paper Sec. 3.4.2: the expert cache is a set of
+    equal-sized slots holding one expert each). slabs[e] is None when expert e is not resident,
     else a flat bf16 array [gate (I x H) | up (I x H) | down (H x I)]. Rows of a non-resident expert are not computed
     (they stay zero); the experts that have rows but no slab are reported, in ascending order.
     Returns (y_sorted [T*k, H], missing list)."""

@@ -204,10 +204,11 @@ const char* moe_status_string(moe_status st) {
         case MOE_ERR_NULL: return "a required pointer is NULL";
         case MOE_ERR_SHAPE: return "inconsistent sizes";
         case MOE_ERR_ALIGN: return "pointer not sufficiently aligned";
-        case MOE_ERR_WORKSPACE: return "no room: the expert cache cannot place a demanded expert";
+        case MOE_ERR_WORKSPACE: return "scratch memory too small for this config";
         case MOE_ERR_UNSUPPORTED: return "shape not supported by this build";
         case MOE_ERR_HIP: return "HIP kernel launch failed";
         case MOE_ERR_INDEX: return "an index array holds an entry out of range";
+        case MOE_ERR_CACHE_FULL: return "no room: the expert cache cannot place a demanded expert";
     }
     return "unknown status";
 }
@@ -224,7 +225,11 @@ moe_status moe_route(const moe_config* cfg, const moe_bf16* x, int32_t T_in, con
     IndexChecker chk((hipStream_t)stream);
     chk.range(keep_idx, T, 0, T_in);
     if ((s = chk.result()) != MOE_OK) return s;
-    return hip_status(launch_route(*cfg, x, keep_idx, T, w_router, topk_ids, topk_w, (hipStream_t)stream), "route");
+    timer_reset();
+    timer_mark(0, 0, (hipStream_t)stream);
+    const hipError_t e = launch_route(*cfg, x, keep_idx, T, w_router, topk_ids, topk_w, (hipStream_t)stream);
+    timer_mark(0, 1, (hipStream_t)stream);
+    return hip_status(e, "route");
 }
 
 moe_status moe_dispatch(const moe_config* cfg, const int32_t* topk_ids, int32_t T, int32_t* expert_offsets,
@@ -240,8 +245,12 @@ moe_status moe_dispatch(const moe_config* cfg, const int32_t* topk_ids, int32_t 
     chk.range(topk_ids, (long long)T * cfg->k, 0, cfg->E);
     if ((s = chk.result()) != MOE_OK) return s;
     // T == 0 still has a defined result: all-zero offsets
-    return hip_status(launch_dispatch(*cfg, topk_ids, T, 0, expert_offsets, sorted_token, inv_perm, w.n_tiles,
-                                      w.tile_map, w.hist, (hipStream_t)stream), "dispatch");
+    timer_reset();
+    timer_mark(1, 0, (hipStream_t)stream);
+    const hipError_t e = launch_dispatch(*cfg, topk_ids, T, 0, expert_offsets, sorted_token, inv_perm, w.n_tiles,
+                                         w.tile_map, w.hist, (hipStream_t)stream);
+    timer_mark(1, 1, (hipStream_t)stream);
+    return hip_status(e, "dispatch");
 }
 
 moe_status moe_expert_ffn(const moe_config* cfg, const moe_bf16* x, int32_t T_in, const int32_t* keep_idx, int32_t T,
@@ -263,6 +272,7 @@ moe_status moe_expert_ffn(const moe_config* cfg, const moe_bf16* x, int32_t T_in
     chk.offsets(expert_offsets, cfg->E, rows);
     chk.range(sorted_token, rows, 0, T);
     if ((s = chk.result()) != MOE_OK) return s;
+    timer_reset();
     if (!use_skinny(rows, cfg->E))
         VISMOE_TRY(launch_tile_map(cfg->E, expert_offsets, w.n_tiles, w.tile_map, st), "tile map");
     return hip_status(run_ffn(*cfg, x, keep_idx, cfg->E, cfg->E, rows, expert_offsets, sorted_token, w.tile_map,
@@ -289,6 +299,7 @@ moe_status moe_expert_ffn_slabs(const moe_config* cfg, const moe_bf16* x, int32_
     chk.offsets(expert_offsets, cfg->E, rows);
     chk.range(sorted_token, rows, 0, T);
     if ((s = chk.result()) != MOE_OK) return s;
+    timer_reset();
     VISMOE_TRY(launch_slab_report(cfg->E, expert_offsets, slab_table, missing, st), "slab report");
     if (!use_skinny(rows, cfg->E))
         VISMOE_TRY(launch_tile_map(cfg->E, expert_offsets, w.n_tiles, w.tile_map, st), "tile map");
@@ -316,12 +327,15 @@ moe_status moe_shared_ffn(const moe_config* cfg, const moe_bf16* x, int32_t T_in
     IndexChecker chk(st);
     chk.range(keep_idx, T, 0, T_in);
     if ((s = chk.result()) != MOE_OK) return s;
+    timer_reset();
     VISMOE_TRY(launch_shared_groups(T, S, w.offsets, w.sorted_token, st), "shared groups");
     if (!use_skinny(rows, S)) VISMOE_TRY(launch_tile_map(S, w.offsets, w.n_tiles, w.tile_map, st), "tile map");
     VISMOE_TRY(run_ffn(*cfg, x, keep_idx, 0, S, rows, w.offsets, w.sorted_token, w.tile_map, w.n_tiles, nullptr, nullptr,
                        nullptr, ws_gate, ws_up, ws_down, w.hm, w.y, st), "shared ffn");
-    return hip_status(launch_combine(nullptr, nullptr, nullptr, T, 0, cfg->H, w.y, S, (long long)T * cfg->H, shared_out,
-                                     st), "shared sum");
+    timer_mark(4, 0, st);
+    const hipError_t ce = launch_combine(nullptr, nullptr, nullptr, T, 0, cfg->H, w.y, S, (long long)T * cfg->H, shared_out, st);
+    timer_mark(4, 1, st);
+    return hip_status(ce, "shared sum");
 }
 
 moe_status moe_combine(const moe_config* cfg, const moe_bf16* y_sorted, const int32_t* inv_perm, const float* topk_w,
@@ -335,8 +349,12 @@ moe_status moe_combine(const moe_config* cfg, const moe_bf16* y_sorted, const in
     IndexChecker chk((hipStream_t)stream);
     chk.range(inv_perm, (long long)T * cfg->k, 0, T * cfg->k);
     if ((s = chk.result()) != MOE_OK) return s;
-    return hip_status(launch_combine(y_sorted, inv_perm, topk_w, T, cfg->k, cfg->H, shared_out, shared_out ? 1 : 0, 0,
-                                     out, (hipStream_t)stream), "combine");
+    timer_reset();
+    timer_mark(4, 0, (hipStream_t)stream);
+    const hipError_t e = launch_combine(y_sorted, inv_perm, topk_w, T, cfg->k, cfg->H, shared_out, shared_out ? 1 : 0, 0,
+                                        out, (hipStream_t)stream);
+    timer_mark(4, 1, (hipStream_t)stream);
+    return hip_status(e, "combine");
 }
 
 moe_status moe_layer_forward(const moe_config* cfg, const moe_bf16* x, int32_t T_in, const int32_t* keep_idx, int32_t T,

@@ -22,14 +22,14 @@ __device__ __forceinline__ int wave_rank_step(int e, bool valid, int nbits, int*
         peers &= bit ? bal : ~bal;
     }
     const unsigned long long lt = (1ull << lane) - 1ull;
-    int rank = 0;
-    if (valid) {
-        const int base = cnt[e];
-        rank = base + __popcll(peers & lt);
-        // all lanes of the wave have issued their read of cnt[e] before the leader's write below (one wave,
-        // LDS operations complete in order)
-        if ((peers & lt) == 0) cnt[e] = base + __popcll(peers);
-    }
+    // every lane reads its counter, then (and only then) the first lane of each group of equal ids writes it back:
+    // the wave barrier keeps the compiler from moving a write above another lane's read; in hardware the LDS
+    // operations of one wave complete in issue order
+    const int base = valid ? cnt[e] : 0;
+    __builtin_amdgcn_wave_barrier();
+    const int rank = base + __popcll(peers & lt);
+    if (valid && (peers & lt) == 0) cnt[e] = base + __popcll(peers);
+    __builtin_amdgcn_wave_barrier();
     return rank;
 }
 

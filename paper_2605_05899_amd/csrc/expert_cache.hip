@@ -218,7 +218,7 @@ moe_status moe_cache_acquire(moe_expert_cache* c, int32_t layer, const int32_t* 
         ++c->stats[1];
         int vl, ve;
         const int slab = take_slab(c, key, &vl, &ve);
-        if (slab < 0) return MOE_ERR_WORKSPACE;      // the cache is too small for what is protected plus this layer
+        if (slab < 0) return MOE_ERR_CACHE_FULL;     // the cache is too small for what is protected plus this layer
         if (start_copy(c, slab, host_src[kv.second], layer, trans) != hipSuccess) return MOE_ERR_HIP;
         c->where[key] = Entry{slab, kRequired, 0.f};      // no prediction scored it
         if (missed_out) missed_out[*n_missed] = kv.first;

@@ -21,7 +21,7 @@ import torch  # noqa: E402,F401
 _lib = ctypes.CDLL(_LIB_PATH)
 
 (MOE_OK, MOE_ERR_NULL, MOE_ERR_SHAPE, MOE_ERR_ALIGN, MOE_ERR_WORKSPACE, MOE_ERR_UNSUPPORTED, MOE_ERR_HIP,
- MOE_ERR_INDEX) = range(8)
+ MOE_ERR_INDEX, MOE_ERR_CACHE_FULL) = range(9)
 
 EXPORTS = ("moe_workspace_bytes", "moe_status_string", "moe_route", "moe_dispatch", "moe_expert_ffn",
            "moe_shared_ffn", "moe_combine", "moe_layer_forward", "moe_stage_timing_enable", "moe_stage_timing_read",

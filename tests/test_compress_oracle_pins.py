@@ -32,6 +32,43 @@ def test_hand_worked_example():
     assert CO.token_compress(A, R, g["E"], g["alpha"], g["beta"], 0.0)["I_keep"].tolist() == e["saliency_only_top5"]
 
 
+def _brute_force(A, R, E, alpha, beta, lam):
+    """The compressor token by token over Python sets and a full sort (Eq. 1-5 as written), sharing nothing with the
+    array formulation of the oracle but the fp32 saliency."""
+    N = A.shape[1]
+    f = np.float32
+    s = CO.normalize(CO.head_mean_saliency(A))
+    K_core, K_keep = int(np.floor(alpha * N)), int(np.floor(beta * N))
+    ranked = sorted(range(N), key=lambda i: (-float(s[i]), i))
+    core = set(ranked[:K_core])
+    experts = [{int(e) for e in R[:, i, :].ravel() if 0 <= int(e) < E} for i in range(N)]
+    target = set().union(*[experts[j] for j in core]) if core else set()
+    score, delta = {}, np.zeros(N, dtype=f)
+    for i in range(N):
+        if i in core:
+            continue
+        if experts[i]:
+            delta[i] = f(len(experts[i] - target)) / f(len(experts[i]))
+        score[i] = f(s[i] - f(f(lam) * delta[i]))
+    rest = sorted(score, key=lambda i: (-float(score[i]), i))[:K_keep - K_core]
+    return sorted(core | set(rest)), delta, score
+
+
+@pytest.mark.parametrize("seed", [10, 11, 12, 13])
+def test_array_formulation_equals_brute_force_over_sets(seed):
+    A, R, E = _random_case(seed, N=211, heads=4, E=40, L=3, k=4)
+    R = R.copy()
+    R[0, ::17, 0] = -1                  # some ids out of range
+    R[1, ::23, 1] = E + 3
+    for alpha, beta, lam in [(0.1, 0.25, 2.0), (0.0, 0.4, 2.0), (0.25, 0.6, 0.7), (0.3, 0.3, 2.0)]:
+        out = CO.token_compress(A, R, E, alpha, beta, lam)
+        keep, delta, score = _brute_force(A, R, E, alpha, beta, lam)
+        assert out["I_keep"].tolist() == keep
+        np.testing.assert_array_equal(out["delta"].view(np.uint32), delta.view(np.uint32))
+        for i, v in score.items():
+            assert np.float32(out["p"][i]).view(np.uint32) == np.float32(v).view(np.uint32)
+
+
 def _random_case(seed, N=157, heads=3, E=24, L=2, k=3):
     c = synth.make_compress_small(seed, N=N, n_heads=heads, E=E, L=L, k=k, n_clusters=4)
     return c.A, c.R, E
@@ -54,7 +91,7 @@ def test_invariants(seed):
         # every core token's experts are in the target set, so a core token would score Delta = 0
         T = set(out["E_target"])
         for j in core:
-            assert CO.active_experts(R, int(j), E) <= T
+            assert {int(e) for e in R[:, int(j), :].ravel() if 0 <= e < E} <= T
 
 
 @pytest.mark.parametrize("seed", [3, 4])
@@ -150,12 +187,14 @@ def _run_mutant(monkeypatch, **patches):
 
 
 def test_mutation_smallest_instead_of_largest(monkeypatch):
-    out, e = _run_mutant(monkeypatch, topk_indices=lambda v, c, K: sorted(c, key=lambda i: (float(v[i]), i))[:K])
+    out, e = _run_mutant(monkeypatch, largest=lambda v, ok, K: np.array(
+        sorted(np.flatnonzero(ok).tolist(), key=lambda i: (float(v[i]), i))[:K], dtype=np.int64))
     assert out["I_keep"].tolist() != e["I_keep"]
 
 
 def test_mutation_only_first_prefix_layer(monkeypatch):
-    out, e = _run_mutant(monkeypatch, active_experts=lambda R, i, E: {int(x) for x in R[0, i, :]})
+    full = CO.membership
+    out, e = _run_mutant(monkeypatch, membership=lambda R, E: full(np.asarray(R)[:1], E))
     assert out["I_keep"].tolist() != e["I_keep"] and not np.allclose(out["delta"], e["delta"])
 
 

@@ -117,7 +117,7 @@ def test_demand_that_cannot_be_placed_and_bad_arguments(env):
     torch, moe = env
     rig = Rig(torch, moe, n_layers=2, E=4, slab_bytes=256, n_slabs=2)
     rig.cache.predict([(0, 0, 0.5), (0, 1, 0.4)], rig.addr, rig.trans)
-    assert rig.cache.acquire(0, [2], rig.addr, rig.trans, rig.comp, check=False) == moe.MOE_ERR_WORKSPACE
+    assert rig.cache.acquire(0, [2], rig.addr, rig.trans, rig.comp, check=False) == moe.MOE_ERR_CACHE_FULL
     assert rig.cache.predict([(0, 0, 0.5), (0, 0, 0.6)], rig.addr, rig.trans, check=False) == moe.MOE_ERR_SHAPE
     assert rig.cache.predict([(2, 0, 0.5)], rig.addr, rig.trans, check=False) == moe.MOE_ERR_SHAPE
     assert rig.cache.acquire(0, [9], rig.addr, rig.trans, rig.comp, check=False) == moe.MOE_ERR_SHAPE
