@@ -136,6 +136,25 @@ moe_status moe_layer_forward(const moe_config* cfg, const moe_bf16* x, int32_t T
                              const moe_bf16* ws_down, moe_bf16* out, int32_t* topk_ids_opt, float* topk_w_opt,
                              void* ws, void* stream);
 
+/* The same layer for callers that cannot allocate and have no workspace to hand over: code under HIP graph capture,
+ * tight serving loops (decode steps), harnesses that forbid hipMalloc. Identical to moe_layer_forward (same kernels,
+ * bit-identical results) except that the scratch memory is a static device array inside the library,
+ * MOE_STATIC_SCRATCH_BYTES per GPU, which each GPU the library runs on holds until the process ends. The call
+ * allocates nothing; the array's device address is looked up once per GPU on the first call there.
+ *   - MOE_ERR_WORKSPACE when moe_workspace_bytes(cfg) exceeds moe_static_scratch_bytes(); nothing is launched.
+ *     (cfg->max_tokens sizes the need: a 64-token decode batch of a 128-expert top-8 layer with H 2048, I 768
+ *     needs 3.2 MB, a pruned 704-token prefill of a 64-expert top-6 layer with two shared experts 39 MB.)
+ *   - Every call on a GPU uses that GPU's one array, which keeps the last call's contents (no call needs it
+ *     cleared): calls that overlap on one GPU, on different streams or from different threads, race. Order them on
+ *     one stream. */
+#define MOE_STATIC_SCRATCH_BYTES (64u << 20)
+size_t moe_static_scratch_bytes(void);
+moe_status moe_layer_forward_static(const moe_config* cfg, const moe_bf16* x, int32_t T_in, const int32_t* keep_idx,
+                                    int32_t T, const moe_bf16* w_router, const moe_bf16* w_gate, const moe_bf16* w_up,
+                                    const moe_bf16* w_down, const moe_bf16* ws_gate, const moe_bf16* ws_up,
+                                    const moe_bf16* ws_down, moe_bf16* out, int32_t* topk_ids_opt, float* topk_w_opt,
+                                    void* stream);
+
 /* Stage timing, a measurement aid for benchmarks (not part of the layer; no passage of the paper defines it).
  * While enabled, every call of the layer (the fused one and the per-step ones) brackets each stage it runs with a
  * pair of HIP events recorded on the call's stream:

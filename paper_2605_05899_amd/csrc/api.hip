@@ -5,9 +5,16 @@
 
 #include <math.h>
 
+#include <mutex>
+
 #include "common.h"
 
 using namespace vismoe;
+
+// Scratch of moe_layer_forward_static: one array per GPU the library is loaded on, held until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress; kernels are given the address that call returns.
+constexpr size_t kStaticScratchBytes = (size_t)MOE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -412,6 +419,46 @@ moe_status moe_layer_forward(const moe_config* cfg, const moe_bf16* x, int32_t T
         launch_combine(w.y, w.inv_perm, gw, T, k, H, w.y + (size_t)T * k * H, S, (long long)T * H, out, st);
     timer_mark(4, 1, st);
     return hip_status(ce, "combine");
+}
+
+// ---- the fused layer for callers that cannot allocate (see moe.h)
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];      // device address of `scratch` on each GPU, resolved on first use
+
+moe_status static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return hip_status(hipGetLastError(), "static scratch: hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return MOE_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return hip_status(e == hipSuccess ? hipErrorInvalidSymbol : e,
+                                                       "static scratch: hipGetSymbolAddress");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MOE_OK;
+}
+}  // namespace
+
+size_t moe_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+moe_status moe_layer_forward_static(const moe_config* cfg, const moe_bf16* x, int32_t T_in, const int32_t* keep_idx,
+                                    int32_t T, const moe_bf16* w_router, const moe_bf16* w_gate, const moe_bf16* w_up,
+                                    const moe_bf16* w_down, const moe_bf16* ws_gate, const moe_bf16* ws_up,
+                                    const moe_bf16* ws_down, moe_bf16* out, int32_t* topk_ids_opt, float* topk_w_opt,
+                                    void* stream) {
+    moe_status s = check_config(cfg);
+    if (s != MOE_OK) return s;
+    if (ws_layout(*cfg).total > kStaticScratchBytes) return MOE_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if ((s = static_scratch(&ws)) != MOE_OK) return s;
+    // Nothing in the workspace has to start at zero: every array in it is written by this call before it is read.
+    return moe_layer_forward(cfg, x, T_in, keep_idx, T, w_router, w_gate, w_up, w_down, ws_gate, ws_up, ws_down, out,
+                             topk_ids_opt, topk_w_opt, ws, stream);
 }
 
 moe_status moe_stage_timing_enable(int32_t enable) {

@@ -28,7 +28,8 @@ EXPORTS = ("moe_workspace_bytes", "moe_status_string", "moe_route", "moe_dispatc
            "moe_compress_workspace_bytes", "moe_token_compress", "moe_expert_ffn_slabs", "moe_mean_pool_workspace_bytes",
            "moe_mean_pool", "moe_routing_histogram", "moe_lookahead_target", "moe_cache_create", "moe_cache_destroy",
            "moe_cache_predict", "moe_cache_acquire", "moe_cache_layer_done", "moe_cache_query", "moe_cache_stats",
-           "moe_predictor_workspace_bytes", "moe_predictor_forward", "moe_index_checks_enable")
+           "moe_predictor_workspace_bytes", "moe_predictor_forward", "moe_index_checks_enable",
+           "moe_static_scratch_bytes", "moe_layer_forward_static")
 N_STAGES = 5
 STAGE_NAMES = ("route", "dispatch", "gate_up_swiglu", "down", "combine")
 
@@ -78,6 +79,10 @@ _lib.moe_combine.restype = ctypes.c_int
 _lib.moe_combine.argtypes = [_CFG, _P, _P, _P, _I32, _P, _P, _P]
 _lib.moe_layer_forward.restype = ctypes.c_int
 _lib.moe_layer_forward.argtypes = [_CFG, _P, _I32, _P, _I32] + [_P] * 12
+_lib.moe_layer_forward_static.restype = ctypes.c_int
+_lib.moe_layer_forward_static.argtypes = [_CFG, _P, _I32, _P, _I32] + [_P] * 11
+_lib.moe_static_scratch_bytes.restype = ctypes.c_size_t
+_lib.moe_static_scratch_bytes.argtypes = []
 _lib.moe_compress_workspace_bytes.restype = ctypes.c_size_t
 _lib.moe_compress_workspace_bytes.argtypes = [_I32, _I32]
 _lib.moe_token_compress.restype = ctypes.c_int
@@ -204,6 +209,18 @@ def moe_layer_forward(cfg, x, T_in, keep_idx, T, w_router, w_gate, w_up, w_down,
                                 _ptr(w_up), _ptr(w_down), _ptr(ws_gate), _ptr(ws_up), _ptr(ws_down), _ptr(out),
                                 _ptr(topk_ids_opt), _ptr(topk_w_opt), _ptr(ws), _stream(stream))
     return _check(st, "moe_layer_forward", check)
+
+
+def moe_static_scratch_bytes() -> int:
+    return int(_lib.moe_static_scratch_bytes())
+
+
+def moe_layer_forward_static(cfg, x, T_in, keep_idx, T, w_router, w_gate, w_up, w_down, ws_gate, ws_up, ws_down, out,
+                             topk_ids_opt, topk_w_opt, stream=None, check=True):
+    st = _lib.moe_layer_forward_static(ctypes.byref(cfg.c()), _ptr(x), T_in, _ptr(keep_idx), T, _ptr(w_router),
+                                       _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(ws_gate), _ptr(ws_up),
+                                       _ptr(ws_down), _ptr(out), _ptr(topk_ids_opt), _ptr(topk_w_opt), _stream(stream))
+    return _check(st, "moe_layer_forward_static", check)
 
 
 def moe_compress_workspace_bytes(N: int, E: int) -> int:
