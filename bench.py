@@ -10,12 +10,15 @@ combine) over one synthetic batch that is already resident in HBM. Prints ONE JS
   roofline        the dominant kernel (grouped gate/up + SwiGLU): algorithmic flops (prefill configs) or bytes
                   (decode config) per launch divided by its mean duration, measured with HIP events recorded on
                   the launch stream around that stage in a second pass of K steps
+  roofline_down   the same for the grouped down projection
+  roofline_layer  the whole layer against the roofline the task's target names for this workload
   cpu_baseline    the CPU oracle timed once on the same inputs on this machine's host cores
   stages_us       mean HIP-event time of every stage (second pass)
   step_event_us   median and minimum over the K steps of the second pass of a step's summed stage event times
-  also            the decode config C5 (the HBM-bound half of the headline metric) measured the same way, when
-                  the main workload is C4; and the affinity-aware token compressor (the producer of the retained-token
-                  index list) on its 8064-token workload
+  also            the other four layer workloads (C1, C2, C3 and the decode config C5, the HBM-bound half of the
+                  headline metric) measured the same way, when the main workload is C4; the affinity-aware token
+                  compressor (the producer of the retained-token index list) on its 8064-token workload; the
+                  predictor features; the expert cache
 """
 import argparse
 import json
@@ -32,25 +35,45 @@ PREWARM_S = 0.1                # untimed spin-up before the warm-up steps (clock
 
 
 def load_traffic(workload, kernel):
-    """Measured HBM bytes per launch from the committed rocprofv3 --pmc summaries, if any."""
+    """Measured HBM bytes per launch from the committed rocprofv3 --pmc summaries, if any, and the commit of the
+    tree they were taken on (a figure from an older tree than the one running is visible as such)."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(workload, {}).get(kernel)
+            j = json.load(f)
+        return j.get(workload, {}).get(kernel), j.get("_meta", {}).get("commit")
     except (OSError, ValueError):
-        return None
+        return None, None
+
+
+def kernel_roofline(workload, kernel, hbm_bound, flops, nbytes, seconds):
+    """Roofline entry of one kernel: algorithmic flops or bytes per launch over its mean event time."""
+    if hbm_bound:
+        roof = {"bound": "hbm", "achieved": nbytes / seconds / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": flops / seconds / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["kernel"] = kernel
+    roof["kernel_us"] = seconds * 1e6
+    tr, commit = load_traffic(workload, kernel)
+    # HBM bytes per launch of that kernel (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy's readings)
+    roof["traffic"] = (tr["fetch_bytes"] + tr["write_bytes"]) if tr else None
+    if tr:
+        roof["traffic_detail"] = tr
+        roof["traffic_commit"] = commit
+    roof["algorithmic_bytes"] = nbytes
+    roof["algorithmic_flops"] = flops
+    return roof
 
 
 def measure(name, steps, warmup, with_cpu_baseline, weight_sets=None):
     import numpy as np
     import torch
-    from paper_2605_05899_amd import moe, synth
-    from tests import helpers as Hp
+    from paper_2605_05899_amd import harness, moe, synth
 
     inp = synth.make_config(name)
-    d = Hp.DeviceLayer(inp, torch, moe)
-    args = (d.cfg, d.x, inp.T_in, d.keep, inp.T, d.w_router, d.w_gate, d.w_up, d.w_down, d.ws_gate, d.ws_up,
-            d.ws_down, d.out, None, None, d.ws)
+    d = harness.DeviceLayer(inp, torch, moe)
+    args = d.layer_args()
     # The weight-streaming configs (C3, C5) rotate over distinct device copies of the layer's weights, one copy per
     # step in turn, so that no step can find the weights of the step before it in the 256 MB last-level cache.
     if weight_sets is None:
@@ -101,28 +124,25 @@ def measure(name, steps, warmup, with_cpu_baseline, weight_sets=None):
     T, H, I, E, k, S = inp.T, inp.H, inp.I, inp.E, inp.k, inp.S
     flops_layer = inp.useful_flops()
     rows = T * (k + S)
-    gate_up_flops = 4.0 * rows * H * I
-    # algorithmic bytes of the gate/up kernel: gate+up weights of every group that has a row, each x row once,
-    # the SwiGLU intermediate written once
+    gate_up_flops, down_flops = 4.0 * rows * H * I, 2.0 * rows * H * I
+    # algorithmic bytes: the weights of every group that has a row, each operand row once, the result once
     gate_up_bytes = (touched + S) * 2.0 * I * H * 2 + T * H * 2 + rows * I * 2
+    down_bytes = (touched + S) * 1.0 * I * H * 2 + rows * I * 2 + rows * H * 2
     layer_bytes = (touched + S) * 3.0 * I * H * 2 + E * H * 2 + 2.0 * T * H * 2
-    gate_up_s = stage_ms[2] * 1e-3
     hbm_bound = name == "C5"
-    if hbm_bound:
-        roof = {"bound": "hbm", "achieved": gate_up_bytes / gate_up_s / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
-    else:
-        roof = {"bound": "mfma", "achieved": gate_up_flops / gate_up_s / 1e12, "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["kernel"] = "ffn_skinny_kernel<0>" if rows <= 40 * (E + S) else "ffn_tile_kernel<0>"
-    roof["kernel_us"] = gate_up_s * 1e6
-    tr = load_traffic(name, roof["kernel"])
-    # HBM bytes per launch of that kernel (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy's readings)
-    roof["traffic"] = (tr["fetch_bytes"] + tr["write_bytes"]) if tr else None
-    if tr:
-        roof["traffic_detail"] = tr
-    roof["algorithmic_bytes"] = gate_up_bytes
-    roof["algorithmic_flops"] = gate_up_flops
+    skinny = rows <= 40 * (E + S)
+    kern = "ffn_skinny_kernel" if skinny else "ffn_tile_kernel"
+    roof = kernel_roofline(name, kern + "<0>", hbm_bound, gate_up_flops, gate_up_bytes, stage_ms[2] * 1e-3)
+    roof_down = kernel_roofline(name, kern + "<1>", hbm_bound, down_flops, down_bytes, stage_ms[3] * 1e-3)
+    step_s = ms_per_step * 1e-3
+    # the whole layer against the roofline its target is stated in: HBM for the decode config and for the pruned
+    # prefill (its small groups re-read every expert's weights for a few rows), MFMA for the other prefill configs
+    layer_hbm = name in ("C3", "C5")
+    roof_layer = ({"bound": "hbm", "achieved": layer_bytes / step_s / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+                  if layer_hbm else
+                  {"bound": "mfma", "achieved": flops_layer / step_s / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"})
+    roof_layer["frac"] = roof_layer["achieved"] / roof_layer["peak"]
+    roof_layer["algorithmic_bytes"], roof_layer["algorithmic_flops"] = layer_bytes, flops_layer
 
     res = {
         "workload": name, "prewarm_steps": prewarm_steps, "weight_sets": weight_sets, "ms_per_step": ms_per_step, "tokens_per_s": T / (ms_per_step * 1e-3),
@@ -130,7 +150,7 @@ def measure(name, steps, warmup, with_cpu_baseline, weight_sets=None):
         "layer_frac_mfma_peak": flops_layer / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "layer_gbs": layer_bytes / (ms_per_step * 1e-3) / 1e9,
         "layer_frac_hbm_peak": layer_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
-        "experts_touched": touched, "roofline": roof,
+        "experts_touched": touched, "roofline": roof, "roofline_down": roof_down, "roofline_layer": roof_layer,
         "stages_us": {n: float(v * 1e3) for n, v in zip(moe.STAGE_NAMES, stage_ms)},
         "step_event_us": {"median": float(np.median(step_event_ms) * 1e3), "min": float(step_event_ms.min() * 1e3)},
         "shape": {"T": T, "T_in": inp.T_in, "H": H, "E": E, "k": k, "I": I, "S": S},
@@ -143,8 +163,10 @@ def measure(name, steps, warmup, with_cpu_baseline, weight_sets=None):
             cores = os.cpu_count() or 1
         # bounded sample: whole-layer oracle passes over the same inputs until about 10 s of CPU time are spent
         reps, t0 = 0, time.perf_counter()
+        from oracle import moe_oracle
         while reps < 1 or (time.perf_counter() - t0 < 10.0 and reps < 20):
-            Hp.oracle_layer(inp)
+            moe_oracle.moe_layer_forward(inp.x, inp.keep_idx, inp.w_router, inp.w_gate, inp.w_up, inp.w_down, inp.k,
+                                         inp.norm_topk, inp.ws_gate, inp.ws_up, inp.ws_down)
             reps += 1
         dt = (time.perf_counter() - t0) / reps
         res["cpu_baseline"] = {"value": T / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
@@ -254,8 +276,7 @@ def measure_expert_cache():
     runs the C4 layer (both streams busy, as in the paper's pipeline)."""
     import numpy as np
     import torch
-    from paper_2605_05899_amd import moe, synth
-    from tests import helpers as Hp
+    from paper_2605_05899_amd import harness, moe, synth
 
     H, I, E, n_fetch = 2048, 768, 64, 48
     slab_bytes = 3 * I * H * 2
@@ -288,9 +309,8 @@ def measure_expert_cache():
     burst()
     alone = [burst() for _ in range(3)]
     inp = synth.make_config("C4")
-    d = Hp.DeviceLayer(inp, torch, moe)
-    args = (d.cfg, d.x, inp.T_in, d.keep, inp.T, d.w_router, d.w_gate, d.w_up, d.w_down, d.ws_gate, d.ws_up, d.ws_down,
-            d.out, None, None, d.ws)
+    d = harness.DeviceLayer(inp, torch, moe)
+    args = d.layer_args()
     layer = lambda: moe.moe_layer_forward(*args, stream=comp)
     busy = [burst(layer) for _ in range(3)]
     return {"slab_MB": slab_bytes / 1e6, "experts_per_burst": n_fetch,
@@ -362,17 +382,22 @@ def main():
         "config": {"workload": a.config, **main_res["shape"], "experts_touched": main_res["experts_touched"]},
         "layer_tflops": main_res["layer_tflops"], "layer_frac_mfma_peak": main_res["layer_frac_mfma_peak"],
         "layer_gbs": main_res["layer_gbs"], "layer_frac_hbm_peak": main_res["layer_frac_hbm_peak"],
-        "roofline": main_res["roofline"], "stages_us": main_res["stages_us"],
+        "roofline": main_res["roofline"], "roofline_down": main_res["roofline_down"],
+        "roofline_layer": main_res["roofline_layer"], "stages_us": main_res["stages_us"],
         "step_event_us": main_res["step_event_us"],
         "prewarm_steps": main_res["prewarm_steps"], "weight_sets": main_res["weight_sets"],
     }
     if "cpu_baseline" in main_res:
         line["cpu_baseline"] = main_res["cpu_baseline"]
     if a.config == "C4" and not a.no_also:
-        c5 = measure("C5", max(a.steps, 50), a.warmup, False)
-        line["also"] = {"C5": {k: c5[k] for k in ("ms_per_step", "tokens_per_s", "layer_gbs", "layer_frac_hbm_peak",
-                                                   "experts_touched", "roofline", "stages_us", "step_event_us",
-                                                   "weight_sets")}}
+        # the other four workloads of the headline metric, same method, no CPU-oracle leg
+        keys = ("ms_per_step", "tokens_per_s", "layer_tflops", "layer_frac_mfma_peak", "layer_gbs",
+                "layer_frac_hbm_peak", "experts_touched", "roofline", "roofline_down", "roofline_layer", "stages_us",
+                "step_event_us", "weight_sets", "prewarm_steps", "shape")
+        line["also"] = {}
+        for other in ("C1", "C2", "C3", "C5"):
+            r = measure(other, max(a.steps, 50), a.warmup, False)
+            line["also"][other] = {k: r[k] for k in keys}
     if not a.no_also:
         line.setdefault("also", {})["token_compress_P2"] = measure_compress("P2", max(a.steps, 200), a.warmup,
                                                                             not a.no_cpu_baseline)

@@ -181,6 +181,7 @@ hipError_t run_ffn(const moe_config& c, const bf16_t* x, const int* keep_idx, in
     p.C = hm; p.ldc = c.I; p.K = c.H; p.N = c.I;
     p.offsets = offsets; p.tile_map = tile_map; p.n_tiles = n_tiles;
     p.n_ntiles = (c.I + 127) / 128;
+    p.n_tall = (c.I + 255) / 256;
     timer_mark(2, 0, st);
     hipError_t e = launch_grouped_gemm(0, skinny, p, rows, st);
     timer_mark(2, 1, st);
@@ -190,6 +191,7 @@ hipError_t run_ffn(const moe_config& c, const bf16_t* x, const int* keep_idx, in
     p.B0 = w_down; p.B1 = nullptr; p.Bs0 = ws_down; p.Bs1 = nullptr;
     p.C = y; p.ldc = c.H; p.K = c.I; p.N = c.H;
     p.n_ntiles = (c.H + 255) / 256;
+    p.n_tall = (c.H + 511) / 512;
     timer_mark(3, 0, st);
     e = launch_grouped_gemm(1, skinny, p, rows, st);
     timer_mark(3, 1, st);
@@ -281,7 +283,8 @@ moe_status moe_expert_ffn(const moe_config* cfg, const moe_bf16* x, int32_t T_in
     if ((s = chk.result()) != MOE_OK) return s;
     timer_reset();
     if (!use_skinny(rows, cfg->E))
-        VISMOE_TRY(launch_tile_map(cfg->E, expert_offsets, w.n_tiles, w.tile_map, st), "tile map");
+        VISMOE_TRY(launch_tile_map(cfg->E, expert_offsets, tall_rows_for(rows, cfg->E, cfg->H, cfg->I), w.n_tiles, w.tile_map,
+                                   st), "tile map");
     return hip_status(run_ffn(*cfg, x, keep_idx, cfg->E, cfg->E, rows, expert_offsets, sorted_token, w.tile_map,
                               w.n_tiles, w_gate, w_up, w_down, nullptr, nullptr, nullptr, w.hm, y_sorted, st),
                       "expert ffn");
@@ -309,7 +312,8 @@ moe_status moe_expert_ffn_slabs(const moe_config* cfg, const moe_bf16* x, int32_
     timer_reset();
     VISMOE_TRY(launch_slab_report(cfg->E, expert_offsets, slab_table, missing, st), "slab report");
     if (!use_skinny(rows, cfg->E))
-        VISMOE_TRY(launch_tile_map(cfg->E, expert_offsets, w.n_tiles, w.tile_map, st), "tile map");
+        VISMOE_TRY(launch_tile_map(cfg->E, expert_offsets, tall_rows_for(rows, cfg->E, cfg->H, cfg->I), w.n_tiles, w.tile_map,
+                                   st), "tile map");
     return hip_status(run_ffn(*cfg, x, keep_idx, cfg->E, cfg->E, rows, expert_offsets, sorted_token, w.tile_map,
                               w.n_tiles, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.hm, y_sorted, st,
                               slab_table),
@@ -336,7 +340,9 @@ moe_status moe_shared_ffn(const moe_config* cfg, const moe_bf16* x, int32_t T_in
     if ((s = chk.result()) != MOE_OK) return s;
     timer_reset();
     VISMOE_TRY(launch_shared_groups(T, S, w.offsets, w.sorted_token, st), "shared groups");
-    if (!use_skinny(rows, S)) VISMOE_TRY(launch_tile_map(S, w.offsets, w.n_tiles, w.tile_map, st), "tile map");
+    if (!use_skinny(rows, S))
+        VISMOE_TRY(launch_tile_map(S, w.offsets, tall_rows_for(rows, S, cfg->H, cfg->I), w.n_tiles, w.tile_map, st),
+                   "tile map");
     VISMOE_TRY(run_ffn(*cfg, x, keep_idx, 0, S, rows, w.offsets, w.sorted_token, w.tile_map, w.n_tiles, nullptr, nullptr,
                        nullptr, ws_gate, ws_up, ws_down, w.hm, w.y, st), "shared ffn");
     timer_mark(4, 0, st);

@@ -21,14 +21,34 @@ constexpr int kMaxS = 8;
 
 // Rows per M-tile of the tiled grouped GEMM; the tile map built by dispatch uses the same constant.
 constexpr int kTileM = 256;
+// A group of at most kTallM rows is computed as "tall" work units instead of a mostly empty M-tile: kTallM tokens
+// against twice as many weight rows (see expert_ffn.hip).
+constexpr int kTallM = 128;
+// Groups of up to this many rows become tall units (at most kTallM; 0 switches the tall path off).
+#ifndef VISMOE_TALL_ROWS
+#define VISMOE_TALL_ROWS 128
+#endif
+constexpr int kTallRows = VISMOE_TALL_ROWS;
+static_assert(kTallRows <= kTallM, "a tall unit holds at most kTallM token rows");
+// Largest group that becomes a tall unit for a launch of `rows` grouped rows in G groups (0: none), decided from the
+// sizes the host knows. Tall units are used when the mean group has at most kTallM rows (pruned prefill: most groups
+// are then single, mostly empty M-tiles whose weight rows nothing else shares) and the launch has more work slots
+// than the chip has CUs (below that, more and smaller workgroups finish sooner). With larger groups in the mix the
+// long tall units only coarsen a schedule of four or five rounds: measured 5 % slower on the 228-rows-per-expert
+// prefill, 11 % faster on the 66-rows-per-expert one.
+static inline int tall_rows_for(long long rows, int G, int H, int I) {
+    if (rows > (long long)kTallM * G) return 0;
+    const long long entries = rows / kTileM + (G + 1) / 2;
+    const long long slots0 = (I + 127) / 128, slots1 = (H + 255) / 256;
+    return entries * (slots0 < slots1 ? slots0 : slots1) > 256 ? kTallRows : 0;
+}
 // Assignments ranked by one workgroup of the multi-block dispatch.
 constexpr int kDispChunk = 1024;
 // Largest T*k handled by the single-workgroup dispatch.
 constexpr int kDispSmallMax = 8192;
-// Small-batch router: logits of the whole batch (T x padded E floats) are held in the LDS of one workgroup, and the
-// contraction is cut into at most kSmallSlices K groups (of four wave slices each) whose partial logits go through
-// the workspace.
-constexpr int kSmallLogits = 16384;
+// Small-batch router (few tokens: decode, small or pruned prefill): the contraction is cut into at most kSmallSlices
+// K groups (of four wave slices each) whose partial logits, T x padded E floats per group, go through the workspace.
+constexpr int kSmallLogits = 65536;
 constexpr int kSmallSlices = 4;
 // Expert count padded to a power of two >= 32 (the fragment width) for the small-batch router.
 static inline int small_route_ep(int E) {
@@ -49,8 +69,8 @@ struct WsLayout {
     size_t offsets;       // int32 [E+S+1]   group offsets: routed experts, then one group per shared expert
     size_t sorted_token;  // int32 [Tm*(k+S)]
     size_t inv_perm;      // int32 [Tm*k]
-    size_t n_tiles;       // int32 [1] (+pad)
-    size_t tile_map;      // int4  [ceil(Tm*(k+S)/kTileM) + E + S]   (group, first row, end row of the group, 0)
+    size_t n_tiles;       // int32 [2] (+pad): number of M-tiles and of tall row blocks in the tile map
+    size_t tile_map;      // int4  [ceil(Tm*(k+S)/kTileM) + E + S]   (group, first row, end row of the group, 1 if tall)
     size_t hist;          // int32 [ceil(Tm*k/kDispChunk) * E]
     size_t partial;       // float [kSmallSlices * kSmallLogits]   K-slices of the small-batch router's logits
     size_t hm;            // bf16  [Tm*(k+S), I]   SwiGLU intermediate
@@ -99,9 +119,10 @@ struct GemmParams {
     int K;
     int N;
     const int* offsets;       // [G+1]
-    const int4* tile_map;     // (group, first row) per M-tile
-    const int* n_tiles;       // number of valid M-tiles
+    const int4* tile_map;     // (group, first row, end row of the group, 1 if tall): the M-tiles, then the tall row blocks
+    const int* n_tiles;       // [0] number of M-tiles, [1] number of tall row blocks
     int n_ntiles;             // column tiles per M-tile
+    int n_tall;               // column units per tall row block
     // Slab-addressed routed experts (nullable): slabs[e] is the device address of expert e's slab or NULL when the
     // expert is not resident; the operands of this GEMM start slab_off0 / slab_off1 elements into the slab.
     const bf16_t* const* slabs;
@@ -132,7 +153,7 @@ hipError_t launch_route(const moe_config& c, const bf16_t* x, const int* keep_id
                         int* topk_ids, float* topk_w, hipStream_t st);
 hipError_t launch_dispatch(const moe_config& c, const int* topk_ids, int T, int n_shared_groups, int* offsets,
                            int* sorted_token, int* inv_perm, int* n_tiles, int4* tile_map, int* hist, hipStream_t st);
-hipError_t launch_tile_map(int G, const int* offsets, int* n_tiles, int4* tile_map, hipStream_t st);
+hipError_t launch_tile_map(int G, const int* offsets, int tall_rows, int* n_tiles, int4* tile_map, hipStream_t st);
 hipError_t launch_route_partial(const moe_config& c, const bf16_t* x, const int* keep_idx, int T, const bf16_t* w_router,
                                 float* partial, int* n_slices_out, hipStream_t st);
 hipError_t launch_route_finish_dispatch(const moe_config& c, const float* partial, int n_slices, int T, int S,

@@ -43,8 +43,9 @@ __device__ __forceinline__ int bits_for(int E) {
 // is unspecified); buf is LDS of blockDim.x ints. The scan itself is
 // done by wave 0 alone, 64 values at a time with a running carry (two workgroup barriers in total instead of two per
 // doubling step).
-__device__ __forceinline__ int block_inclusive_scan(int v, int* buf, int tid, int n_valid) {
-    buf[tid] = v;
+// Thread tid contributes at position pos (a permutation of the thread indices) and gets the sum up to that position.
+__device__ __forceinline__ int block_inclusive_scan_at(int v, int pos, int* buf, int tid, int n_valid) {
+    buf[pos] = v;
     __syncthreads();
     if (tid < 64) {
         int carry = 0;
@@ -61,13 +62,48 @@ __device__ __forceinline__ int block_inclusive_scan(int v, int* buf, int tid, in
         }
     }
     __syncthreads();
-    return buf[tid];
+    return buf[pos];
+}
+__device__ __forceinline__ int block_inclusive_scan(int v, int* buf, int tid, int n_valid) {
+    return block_inclusive_scan_at(v, tid, buf, tid, n_valid);
 }
 
-// Writes offsets[0..G], the tile map and n_tiles from per-group counts (one group per thread, G <= blockDim.x).
+// The work of a group of cnt rows: a group of at most tall_rows rows is one tall row block; any other group is cut
+// into M-tiles of kTileM rows (the last one partial). Only whole groups go the tall way: the partial last M-tile of a
+// larger group walks K in step with the group's other M-tiles and finds their weight rows in L2, which a tall unit,
+// covering two column tiles at a pace of its own, would fetch from HBM again (measured: 30 us slower on the
+// 512-rows-per-expert prefill when remainders were made tall).
+__device__ __forceinline__ void group_tiles(int cnt, int tall_rows, int& n_mtiles, int& has_tall) {
+    has_tall = (cnt > 0 && cnt <= tall_rows) ? 1 : 0;
+    n_mtiles = has_tall ? 0 : (cnt + kTileM - 1) / kTileM;
+}
+
+// Tile map from per-group (offset, count), one group per thread (G <= blockDim.x): first the M-tiles of all groups,
+// group-major, then the tall row blocks of all groups. n_tiles[0] and n_tiles[1] count the two parts.
+__device__ void emit_tiles(int off, int cnt, int G, int tall_rows, int* s_scan, int* n_tiles, int4* tile_map) {
+    const int tid = threadIdx.x;
+    int tiles = 0, tall = 0;
+    if (tid < G) group_tiles(cnt, tall_rows, tiles, tall);
+    const int tinc = block_inclusive_scan(tiles, s_scan, tid, G);
+    const int n_big = s_scan[G - 1];
+    __syncthreads();
+    const int ainc = block_inclusive_scan(tall, s_scan, tid, G);
+    if (tid < G) {
+        const int tfirst = tinc - tiles;
+        for (int i = 0; i < tiles; ++i) tile_map[tfirst + i] = make_int4(tid, off + i * kTileM, off + cnt, 0);
+        if (tall) tile_map[n_big + ainc - 1] = make_int4(tid, off, off + cnt, 1);
+        if (tid == G - 1) {
+            n_tiles[0] = n_big;
+            n_tiles[1] = ainc;
+        }
+    }
+    __syncthreads();
+}
+
+// Writes offsets[0..G], the tile maps and n_tiles from per-group counts (one group per thread, G <= blockDim.x).
 // Groups [E, G) are the shared experts: T rows each.
-__device__ void emit_offsets_and_tiles(int my_count, int G, int* s_scan, int* offsets, int* n_tiles, int4* tile_map,
-                                       int* s_off /*LDS [G+1] or null*/) {
+__device__ void emit_offsets_and_tiles(int my_count, int G, int tall_rows, int* s_scan, int* offsets, int* n_tiles,
+                                       int4* tile_map, int* s_off /*LDS [G+1] or null*/) {
     const int tid = threadIdx.x;
     const int cnt = (tid < G) ? my_count : 0;
     const int inc = block_inclusive_scan(cnt, s_scan, tid, G);
@@ -81,14 +117,7 @@ __device__ void emit_offsets_and_tiles(int my_count, int G, int* s_scan, int* of
         }
     }
     __syncthreads();
-    const int tiles = (cnt + kTileM - 1) / kTileM;
-    const int tinc = block_inclusive_scan(tiles, s_scan, tid, G);
-    const int tfirst = tinc - tiles;
-    if (tid < G) {
-        for (int i = 0; i < tiles; ++i) tile_map[tfirst + i] = make_int4(tid, off + i * kTileM, off + cnt, 0);
-        if (tid == G - 1) n_tiles[0] = tinc;
-    }
-    __syncthreads();
+    emit_tiles(off, cnt, G, tall_rows, s_scan, n_tiles, tile_map);
 }
 
 // ---------------------------------------------------------------- small path: one workgroup of 1024 threads
@@ -96,7 +125,7 @@ constexpr int kSmallWaves = 16, kSmallPerWave = kDispSmallMax / kSmallWaves, kSm
 
 // The whole dispatch for T*k <= kDispSmallMax inside one workgroup of 1024 threads (512 assignments per wave in 8
 // steps). LDS: s_cnt [16 * E], s_scan [1024], s_off [E + S + 1].
-__device__ __forceinline__ void dispatch_small_body(const int* __restrict__ ids, int T, int k, int E, int S,
+__device__ __forceinline__ void dispatch_small_body(const int* __restrict__ ids, int T, int k, int E, int S, int tall_rows,
                                                     int* __restrict__ offsets, int* __restrict__ sorted_token,
                                                     int* __restrict__ inv_perm, int* __restrict__ n_tiles,
                                                     int4* __restrict__ tile_map, int* s_cnt, int* s_scan, int* s_off) {
@@ -136,7 +165,7 @@ __device__ __forceinline__ void dispatch_small_body(const int* __restrict__ ids,
     }
     const int my_count = (tid < E) ? total : T;     // shared groups hold every token
     __syncthreads();
-    emit_offsets_and_tiles(my_count, G, s_scan, offsets, n_tiles, tile_map, s_off);
+    emit_offsets_and_tiles(my_count, G, tall_rows, s_scan, offsets, n_tiles, tile_map, s_off);
 
 #pragma unroll
     for (int it = 0; it < kSmallIter; ++it) {
@@ -152,13 +181,15 @@ __device__ __forceinline__ void dispatch_small_body(const int* __restrict__ ids,
 }
 
 __global__ __launch_bounds__(1024) void dispatch_small_kernel(const int* __restrict__ ids, int T, int k, int E, int S,
+                                                              int tall_rows,
                                                               int* __restrict__ offsets, int* __restrict__ sorted_token,
                                                               int* __restrict__ inv_perm, int* __restrict__ n_tiles,
                                                               int4* __restrict__ tile_map) {
     __shared__ int s_cnt[kSmallWaves * kMaxE];
     __shared__ int s_scan[1024];
     __shared__ int s_off[kMaxE + kMaxS + 1];
-    dispatch_small_body(ids, T, k, E, S, offsets, sorted_token, inv_perm, n_tiles, tile_map, s_cnt, s_scan, s_off);
+    dispatch_small_body(ids, T, k, E, S, tall_rows, offsets, sorted_token, inv_perm, n_tiles, tile_map, s_cnt, s_scan,
+                        s_off);
 }
 
 // ---------------------------------------------------------------- small batches: router finish, then dispatch
@@ -204,10 +235,11 @@ hipError_t launch_route_finish_dispatch(const moe_config& c, const float* partia
     do {                                                                                                            \
         hipLaunchKernelGGL(route_topk_small_kernel<EP>, dim3((T + 3) / 4), dim3(64), 0, st, partial, n_slices, T, c.k, \
                            c.E, c.norm_topk, topk_ids, topk_w);                                                     \
-        hipLaunchKernelGGL(dispatch_small_kernel, dim3(1), dim3(1024), 0, st, topk_ids, T, c.k, c.E, S, offsets,     \
-                           sorted_token, inv_perm, n_tiles, tile_map);                                              \
+        hipLaunchKernelGGL(dispatch_small_kernel, dim3(1), dim3(1024), 0, st, topk_ids, T, c.k, c.E, S, tall_rows,   \
+                           offsets, sorted_token, inv_perm, n_tiles, tile_map);                                     \
     } while (0)
     const int ep = small_route_ep(c.E);
+    const int tall_rows = tall_rows_for((long long)T * (c.k + S), c.E + S, c.H, c.I);
     if (ep == 32) VISMOE_RFD(32);
     else if (ep == 64) VISMOE_RFD(64);
     else if (ep == 128) VISMOE_RFD(128);
@@ -259,6 +291,7 @@ __global__ __launch_bounds__(256) void dispatch_rank_kernel(const int* __restric
 
 // Step 2: per expert, exclusive prefix of the chunk histograms over chunks (in place); then offsets + tile map.
 __global__ __launch_bounds__(1024) void dispatch_scan_kernel(int* __restrict__ hist, int n_chunks, int T, int E, int S,
+                                                             int tall_rows,
                                                              int* __restrict__ offsets, int* __restrict__ n_tiles,
                                                              int4* __restrict__ tile_map) {
     __shared__ int s_scan[1024];
@@ -277,7 +310,7 @@ __global__ __launch_bounds__(1024) void dispatch_scan_kernel(int* __restrict__ h
         }
     }
     const int my_count = (tid < E) ? total : T;
-    emit_offsets_and_tiles(my_count, E + S, s_scan, offsets, n_tiles, tile_map, nullptr);
+    emit_offsets_and_tiles(my_count, E + S, tall_rows, s_scan, offsets, n_tiles, tile_map, nullptr);
 }
 
 // Step 3: final positions.
@@ -301,14 +334,15 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(const int* __rest
 hipError_t launch_dispatch(const moe_config& c, const int* topk_ids, int T, int n_shared_groups, int* offsets,
                            int* sorted_token, int* inv_perm, int* n_tiles, int4* tile_map, int* hist, hipStream_t st) {
     const int N = T * c.k, S = n_shared_groups;
+    const int tall_rows = tall_rows_for((long long)T * (c.k + S), c.E + S, c.H, c.I);
     if (N <= kDispSmallMax) {
-        hipLaunchKernelGGL(dispatch_small_kernel, dim3(1), dim3(1024), 0, st, topk_ids, T, c.k, c.E, S, offsets,
+        hipLaunchKernelGGL(dispatch_small_kernel, dim3(1), dim3(1024), 0, st, topk_ids, T, c.k, c.E, S, tall_rows, offsets,
                            sorted_token, inv_perm, n_tiles, tile_map);
         return hipGetLastError();
     }
     const int n_chunks = (N + kDispChunk - 1) / kDispChunk;
     hipLaunchKernelGGL(dispatch_rank_kernel, dim3(n_chunks), dim3(256), 0, st, topk_ids, N, c.E, inv_perm, hist);
-    hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(1024), 0, st, hist, n_chunks, T, c.E, S, offsets, n_tiles,
+    hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(1024), 0, st, hist, n_chunks, T, c.E, S, tall_rows, offsets, n_tiles,
                        tile_map);
     const int total = N + S * T;
     hipLaunchKernelGGL(dispatch_scatter_kernel, dim3((total + 255) / 256), dim3(256), 0, st, topk_ids, T, c.k, c.E, S,
@@ -317,7 +351,8 @@ hipError_t launch_dispatch(const moe_config& c, const int* topk_ids, int T, int 
 }
 
 // Tile map from existing offsets (used when the caller brings its own expert_offsets).
-__global__ __launch_bounds__(1024) void tile_map_kernel(int G, const int* __restrict__ offsets, int* __restrict__ n_tiles,
+__global__ __launch_bounds__(1024) void tile_map_kernel(int G, const int* __restrict__ offsets, int tall_rows,
+                                                        int* __restrict__ n_tiles,
                                                         int4* __restrict__ tile_map) {
     __shared__ int s_scan[1024];
     const int tid = threadIdx.x;
@@ -326,17 +361,11 @@ __global__ __launch_bounds__(1024) void tile_map_kernel(int G, const int* __rest
         off = offsets[tid];
         cnt = offsets[tid + 1] - off;
     }
-    const int tiles = (cnt + kTileM - 1) / kTileM;
-    const int tinc = block_inclusive_scan(tiles, s_scan, tid, G);
-    const int tfirst = tinc - tiles;
-    if (tid < G) {
-        for (int i = 0; i < tiles; ++i) tile_map[tfirst + i] = make_int4(tid, off + i * kTileM, off + cnt, 0);
-        if (tid == G - 1) n_tiles[0] = tinc;
-    }
+    emit_tiles(off, cnt, G, tall_rows, s_scan, n_tiles, tile_map);
 }
 
-hipError_t launch_tile_map(int G, const int* offsets, int* n_tiles, int4* tile_map, hipStream_t st) {
-    hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(1024), 0, st, G, offsets, n_tiles, tile_map);
+hipError_t launch_tile_map(int G, const int* offsets, int tall_rows, int* n_tiles, int4* tile_map, hipStream_t st) {
+    hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(1024), 0, st, G, offsets, tall_rows, n_tiles, tile_map);
     return hipGetLastError();
 }
 

@@ -157,6 +157,47 @@ __device__ __forceinline__ void slab_step(lds_bf16* __restrict__ ca, lds_bf16* _
     __builtin_amdgcn_sched_barrier(0);
 }
 
+// Epilogue of a wave's 128 x 128 sub-tile: lane = token r of fragment t; registers i = output columns 16*q + i of
+// fragment j. MODE 0 applies SwiGLU to the gate (j = 0, 1) and up (j = 2, 3) sums of the same columns.
+template <int MODE, int NT>
+__device__ __forceinline__ void store_acc(const GemmParams& p, const floatx16 (&acc)[4][4], int m_first, int m_end,
+                                          int n_first, int q) {
+    const int r = threadIdx.x & 31;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int row = m_first + t * 32 + r;
+        if (row >= m_end) continue;
+        bf16_t* crow = p.C + (size_t)row * p.ldc;
+        if (MODE == 0) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int col = n_first + j * 32 + 16 * q;
+                if (col >= p.N) continue;
+                uint32_t o[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float h0 = silu_f(acc[t][j][2 * e]) * acc[t][j + 2][2 * e];
+                    const float h1 = silu_f(acc[t][j][2 * e + 1]) * acc[t][j + 2][2 * e + 1];
+                    o[e] = pack_bf16x2(h0, h1);
+                }
+                *reinterpret_cast<uint4*>(crow + col) = make_uint4(o[0], o[1], o[2], o[3]);
+                *reinterpret_cast<uint4*>(crow + col + 8) = make_uint4(o[4], o[5], o[6], o[7]);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = n_first + j * 32 + 16 * q;
+                if (col >= p.N) continue;
+                uint32_t o[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = pack_bf16x2(acc[t][j][2 * e], acc[t][j][2 * e + 1]);
+                *reinterpret_cast<uint4*>(crow + col) = make_uint4(o[0], o[1], o[2], o[3]);
+                *reinterpret_cast<uint4*>(crow + col + 8) = make_uint4(o[4], o[5], o[6], o[7]);
+            }
+        }
+    }
+}
+
 template <int MODE, int NT>
 __device__ __forceinline__ void tile_body(const GemmParams& p, const TileCtx& c, lds_bf16* G0, lds_bf16* G1, lds_bf16* G2,
                                           lds_bf16* G3, lds_bf16* G4, int m_first, int m_end, int n_first) {
@@ -201,40 +242,227 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const TileCtx& c,
 #undef VISMOE_SLAB
     __builtin_amdgcn_s_waitcnt(0x0070);      // no load may still be writing LDS when the workgroup releases it
 
-    // ---- epilogue: lane = token r of fragment t; registers i = output columns 16*q + i of fragment j
-    const int r = threadIdx.x & 31, q = c.q;
+    store_acc<MODE, NT>(p, acc, m_first, m_end, n_first, c.q);
+}
+
+// ---------------------------------------------------------------------------------------------- tall work units
+// A group of at most kTallM = 128 rows would fill an M-tile less than half while its workgroups still stream a full
+// tile's weight rows. Such groups are computed as tall units instead: 128 tokens against
+// 512 weight rows (MODE 0: 256 gate + 256 up rows = 256 output columns; MODE 1: 512 output columns), half as many
+// workgroups per group, each weight row still read once, the token rows read half as often. The four waves sit
+// side by side: every wave multiplies all 128 tokens with its own 128 weight rows, i.e. the same 4 x 4 fragments per
+// wave as in an M-tile. A wave's weight rows are its private business (it requests them and is the only one to
+// read them), the token rows are shared. LDS = ten 16 KB blocks: tokens of the slab being multiplied and of the next
+// one, and per wave its weight rows of the two slabs. One barrier per slab: behind it every wave has finished with
+// the current blocks and the next slab has landed, so the blocks just freed are requested again at once (slab i + 2)
+// and stay in flight for a whole slab time.
+constexpr int kTallBlockElems = kTallM * BK;      // 16 KB
+
+struct TallCtx {
+    const bf16_t* a_base;
+    const bf16_t* b_base[2];   // the matrix feeding fragments 0, 1 and 2, 3 of the wave (MODE 0: gate / up)
+    int a_off[4];              // element offsets of this lane's 4 token rows (rows 32 wave + 8 j + lane / 8), swizzled chunk
+    int b_off[16];             // ... and of its 16 weight rows (rows 8 j + lane / 8 of the wave's block)
+    int tok_blk;               // element offset of the 1 KB pieces this wave fills in a token block
+    int a_row, b_row[4];
+    int key, q, k_last;
+};
+
+__device__ __forceinline__ void tall_issue_tokens(lds_bf16* __restrict__ tok, int k0, const TallCtx& c) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int row = m_first + t * 32 + r;
-        if (row >= m_end) continue;
-        bf16_t* crow = p.C + (size_t)row * p.ldc;
-        if (MODE == 0) {
+    for (int j = 0; j < 4; ++j)
+        __builtin_amdgcn_global_load_lds((gptr_t)(c.a_base + c.a_off[j] + k0), (lptr_t)(tok + c.tok_blk + j * 512), 16, 0, 0);
+}
+__device__ __forceinline__ void tall_issue_weights(lds_bf16* __restrict__ wts, int k0, const TallCtx& c) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int col = n_first + j * 32 + 16 * q;
-                if (col >= p.N) continue;
-                uint32_t o[8];
+    for (int j = 0; j < 16; ++j)
+        __builtin_amdgcn_global_load_lds((gptr_t)(c.b_base[j >> 3] + c.b_off[j] + k0), (lptr_t)(wts + j * 512), 16, 0, 0);
+}
+
+// Half of the MFMAs of a k-step (token fragments [HALF NT/2, (HALF+1) NT/2)).
+template <int NT, int HALF>
+__device__ __forceinline__ void mma_half(const Frags& f, floatx16 (&acc)[4][4]) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float h0 = silu_f(acc[t][j][2 * e]) * acc[t][j + 2][2 * e];
-                    const float h1 = silu_f(acc[t][j][2 * e + 1]) * acc[t][j + 2][2 * e + 1];
-                    o[e] = pack_bf16x2(h0, h1);
-                }
-                *reinterpret_cast<uint4*>(crow + col) = make_uint4(o[0], o[1], o[2], o[3]);
-                *reinterpret_cast<uint4*>(crow + col + 8) = make_uint4(o[4], o[5], o[6], o[7]);
-            }
-        } else {
+    for (int t = HALF * NT / 2; t < (HALF + 1) * NT / 2; ++t)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int col = n_first + j * 32 + 16 * q;
-                if (col >= p.N) continue;
-                uint32_t o[8];
+        for (int j = 0; j < 4; ++j)
+            acc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.w[j], f.x[t], acc[t][j], 0, 0, 0);
+}
+
+template <int NT>
+__device__ __forceinline__ void tall_read(const lds_bf16* __restrict__ tok, const lds_bf16* __restrict__ wts, int ks,
+                                          const TallCtx& c, Frags& f) {
+    const int ch = ((ks * 2 + c.q) ^ c.key) * 8;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) o[e] = pack_bf16x2(acc[t][j][2 * e], acc[t][j][2 * e + 1]);
-                *reinterpret_cast<uint4*>(crow + col) = make_uint4(o[0], o[1], o[2], o[3]);
-                *reinterpret_cast<uint4*>(crow + col + 8) = make_uint4(o[4], o[5], o[6], o[7]);
-            }
+    for (int t = 0; t < NT; ++t) f.x[t] = *reinterpret_cast<lds_frag_ptr>(tok + c.a_row + t * 32 * BK + ch);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) f.w[j] = *reinterpret_cast<lds_frag_ptr>(wts + c.b_row[j] + ch);
+}
+
+// Instruction order of a tall k-step (or half of one): MFMAs with `reads` fragment reads and `loads` direct-to-LDS
+// loads spread between them.
+template <int MFMAS, int READS, int LOADS>
+__device__ __forceinline__ void pin_tall() {
+    if (MFMAS == 0) return;
+    constexpr int M = MFMAS > 0 ? MFMAS : 1;
+    constexpr int RP = (READS + M - 1) / M, LP = (LOADS + M - 1) / M;                    // per MFMA
+#pragma unroll
+    for (int n = 0; n < MFMAS; ++n) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                             // MFMA
+        if (RP > 0 && n * RP < READS) __builtin_amdgcn_sched_group_barrier(0x100, RP, 0);    // DS read
+        if (LP > 0 && n * LP < LOADS) __builtin_amdgcn_sched_group_barrier(0x020, LP, 0);    // direct-to-LDS load
+    }
+}
+
+// One slab i held in (tc, wc); slab i + 1 has been requested into (tn, wn). On entry f0 holds the k-step 0 fragments.
+// The wave's own weight block is requested again (slab i + 2) as soon as the wave has read its last fragments from
+// it, before the barrier, so that loads are in flight while the waves wait for each other; the token block is shared
+// and follows behind the barrier.
+template <int NT>
+__device__ __forceinline__ void tall_step(lds_bf16* __restrict__ tc, lds_bf16* __restrict__ wc, lds_bf16* __restrict__ tn,
+                                          lds_bf16* __restrict__ wn, int k2, const TallCtx& c, Frags& f0, Frags& f1,
+                                          floatx16 (&acc)[4][4]) {
+    if (NT > 0) tall_read<NT>(tc, wc, 1, c, f1);
+    mma_step<NT>(f0, acc);
+    pin_tall<4 * NT, 4 + NT, 0>();
+    __builtin_amdgcn_sched_barrier(0);
+    if (NT > 0) tall_read<NT>(tc, wc, 2, c, f0);
+    mma_step<NT>(f1, acc);
+    pin_tall<4 * NT, 4 + NT, 0>();
+    __builtin_amdgcn_sched_barrier(0);
+    if (NT > 0) tall_read<NT>(tc, wc, 3, c, f1);
+    mma_half<NT, 0>(f0, acc);
+    pin_tall<2 * NT, 4 + NT, 0>();
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): this wave's reads of wc have returned
+    tall_issue_weights(wc, k2, c);
+    mma_half<NT, 1>(f0, acc);
+    pin_tall<2 * NT, 0, 16>();
+    __builtin_amdgcn_sched_barrier(0);
+    // slab i + 1 has landed (this wave's share): all loads but the 16 just issued: vmcnt(16)
+    __builtin_amdgcn_s_waitcnt(0x4F70);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    tall_issue_tokens(tc, k2, c);
+    if (NT > 0) tall_read<NT>(tn, wn, 0, c, f0);
+    mma_step<NT>(f1, acc);
+    pin_tall<4 * NT, 4 + NT, 4>();
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int MODE, int NT>
+__device__ __forceinline__ void tall_body(const GemmParams& p, const TallCtx& c, lds_bf16* T0, lds_bf16* T1, lds_bf16* W0,
+                                          lds_bf16* W1, int m0, int m_end, int n_first) {
+    floatx16 acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+    const int KT = p.K / BK;
+    auto slab_k = [&](int i) { return min(i * BK, c.k_last); };
+    // every step requests one slab (past the end of K the last one again), so the loads in flight behind a wait are
+    // the same on every path
+    tall_issue_tokens(T0, 0, c);
+    tall_issue_weights(W0, 0, c);
+    tall_issue_tokens(T1, slab_k(1), c);
+    tall_issue_weights(W1, slab_k(1), c);
+    __builtin_amdgcn_s_waitcnt(0x4070 | 4);      // vmcnt(20): slab 0 has landed, slab 1 may be in flight
+    __builtin_amdgcn_s_barrier();
+    Frags f0, f1;
+    if (NT > 0) tall_read<NT>(T0, W0, 0, c, f0);
+    int i = 0;
+    for (; i + 2 <= KT; i += 2) {
+        tall_step<NT>(T0, W0, T1, W1, slab_k(i + 2), c, f0, f1, acc);
+        tall_step<NT>(T1, W1, T0, W0, slab_k(i + 3), c, f0, f1, acc);
+    }
+    if (i < KT) tall_step<NT>(T0, W0, T1, W1, slab_k(i + 2), c, f0, f1, acc);
+    __builtin_amdgcn_s_waitcnt(0x0070);      // no load may still be writing LDS when the workgroup releases it
+    store_acc<MODE, NT>(p, acc, m0, m_end, n_first, c.q);
+}
+
+template <int MODE>
+__device__ __forceinline__ void tall_run(int nt, const GemmParams& p, const TallCtx& c, lds_bf16* T0, lds_bf16* T1,
+                                         lds_bf16* W0, lds_bf16* W1, int m0, int m_end, int n_first) {
+    if (nt == 4) tall_body<MODE, 4>(p, c, T0, T1, W0, W1, m0, m_end, n_first);
+    else if (nt == 2) tall_body<MODE, 2>(p, c, T0, T1, W0, W1, m0, m_end, n_first);
+    else tall_body<MODE, 0>(p, c, T0, T1, W0, W1, m0, m_end, n_first);
+}
+
+// One tall unit: column unit n_unit of the row block tm = (group, first row, end row).
+template <int MODE>
+__device__ __forceinline__ void tall_unit(const GemmParams& p, const int4 tm, int n_unit, lds_bf16* G0, lds_bf16* G1,
+                                          lds_bf16* G2, lds_bf16* G3, lds_bf16* G4) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 31, q = lane >> 5;
+    const int g = tm.x, m0 = tm.y, m_end = tm.z;            // 1 <= m_end - m0 <= kTallM
+    constexpr int BNU = (MODE == 0) ? 256 : 512;            // output columns per unit
+    constexpr int BNW = BNU / 4;                            // ... per wave
+    const int n0 = n_unit * BNU;
+    const int K = p.K, N = p.N;
+    const bf16_t *b0, *b1;
+    if (!group_weights(p, g, MODE == 0, b0, b1)) {
+        // expert not resident: its part of the output is defined as zero (the caller is told which experts)
+        const int rows = m_end - m0, cols = min(BNU, N - n0);
+        for (int i = tid; i < rows * (cols / 8); i += 256) {
+            const int rr = i / (cols / 8), cc = (i - rr * (cols / 8)) * 8;
+            *reinterpret_cast<uint4*>(p.C + (size_t)(m0 + rr) * p.ldc + n0 + cc) = make_uint4(0, 0, 0, 0);
         }
+        return;
+    }
+    TallCtx c;
+    c.q = q;
+    c.key = (r >> 1) & 7;
+    c.k_last = K - BK;
+    c.a_base = p.A;
+    c.b_base[0] = b0;
+    c.b_base[1] = b1;
+    c.tok_blk = wave * (32 * BK);
+    const int lrow = lane >> 3, lpos = lane & 7;
+    const int n_first = n0 + wave * BNW;                    // first output column of this wave
+    // weight rows of the wave's private block: block row m = 32 f + rr holds, for fragment f,
+    //   MODE 0: f = 0, 1 gate rows and f = 2, 3 up rows of output columns n_first + 32 (f & 1) + frag_perm(rr)
+    //   MODE 1: down rows n_first + 32 f + frag_perm(rr)
+    // Columns past N are clamped and never stored.
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const int rr = 8 * (j & 3) + lrow, f = j >> 2;
+        const int chunk = (lpos ^ ((rr >> 1) & 7)) * 8;
+        const int col = (MODE == 0) ? n_first + 32 * (f & 1) + frag_perm(rr) : n_first + 32 * f + frag_perm(rr);
+        c.b_off[j] = min(col, N - 1) * K + chunk;
+    }
+    // token rows 32 wave + 8 j + lrow of the block; rows past the end of the group repeat its last row
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int rr = 8 * j + lrow;
+        const int chunk = (lpos ^ ((rr >> 1) & 7)) * 8;
+        int arow = min(m0 + 32 * wave + rr, m_end - 1);
+        if (MODE == 0) {
+            arow = p.sorted_token[arow];
+            if (p.keep_idx) arow = p.keep_idx[arow];
+        }
+        c.a_off[j] = arow * p.lda + chunk;
+    }
+    c.a_row = r * BK;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c.b_row[j] = (32 * j + r) * BK;
+    // LDS blocks. The compiler lets a fragment read overtake the loads in flight only when it can tell that they
+    // touch different __shared__ arrays, so for every wave the blocks of one slab parity (tokens and its weights) and
+    // those of the other parity must lie in different arrays, with pointers that are constants of the code path:
+    //   G0 = [tokens even | wave 0 even]   G1 = [tokens odd | wave 0 odd]   G2 = [wave 1 even | wave 2 even]
+    //   G3 = [wave 1 odd | wave 3 odd]     G4 = [wave 3 even | wave 2 odd]
+    constexpr int HB = kTallBlockElems;
+    // a wave whose columns all lie past N (last, ragged unit) multiplies nothing but keeps loading and synchronising;
+    // one or three live token fragments run as two or four (the dead rows repeat the last live row)
+    const int live = (m_end - m0 + 31) >> 5;
+    const int nt = __builtin_amdgcn_readfirstlane(n_first >= N ? 0 : (live <= 2 ? 2 : 4));
+    switch (wave) {
+        case 0: tall_run<MODE>(nt, p, c, G0, G1, G0 + HB, G1 + HB, m0, m_end, n_first); break;
+        case 1: tall_run<MODE>(nt, p, c, G0, G1, G2, G3, m0, m_end, n_first); break;
+        case 2: tall_run<MODE>(nt, p, c, G0, G1, G2 + HB, G4 + HB, m0, m_end, n_first); break;
+        default: tall_run<MODE>(nt, p, c, G0, G1, G4, G3 + HB, m0, m_end, n_first); break;
     }
 }
 
@@ -251,17 +479,36 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int r = lane & 31, q = lane >> 5;
 
     // Workgroups are spread over the 8 XCDs round-robin by the hardware; give each XCD one contiguous run of
-    // the (group-major) tile list so that tiles sharing weights or tokens share an L2.
-    const int n_work = p.n_tiles[0] * p.n_ntiles;
-    const int per_xcd = (n_work + 7) >> 3;
-    const int slot = blockIdx.x >> 3;
-    if (slot >= per_xcd) return;
+    // the (group-major) list of M-tile work and one of the list of tall units, so that tiles sharing weights or
+    // tokens share an L2 and both kinds of work are spread evenly over the XCDs.
+    const int n_mt = p.n_tiles[0];
+    const int n_work = n_mt * p.n_ntiles, n_tall_work = p.n_tiles[1] * p.n_tall;
+    const int per_xcd = (n_work + 7) >> 3, per_xcd_tall = (n_tall_work + 7) >> 3;
+    int slot = blockIdx.x >> 3;
+    if (slot >= per_xcd + per_xcd_tall) return;
     // MODE 1 walks every XCD's run backwards: the rows of the intermediate that this XCD wrote last (in MODE 0, which
     // walks the same runs forwards) are read first, while they are still in its L2.
-    const int work = (blockIdx.x & 7) * per_xcd + ((MODE == 1) ? per_xcd - 1 - slot : slot);
+    if (MODE == 1) slot = per_xcd + per_xcd_tall - 1 - slot;
+    lds_bf16* const G0 = (lds_bf16*)g0; lds_bf16* const G1 = (lds_bf16*)g1; lds_bf16* const G2 = (lds_bf16*)g2;
+    lds_bf16* const G3 = (lds_bf16*)g3; lds_bf16* const G4 = (lds_bf16*)g4;
+    // an XCD works through its tall units first (they take longest), then through its M-tiles (MODE 1: the other
+    // way round)
+    if (slot < per_xcd_tall) {
+        const int unit = (blockIdx.x & 7) * per_xcd_tall + slot;
+        if (unit >= n_tall_work) return;
+        const int blk = unit / p.n_tall;
+        tall_unit<MODE>(p, p.tile_map[n_mt + blk], unit - blk * p.n_tall, G0, G1, G2, G3, G4);
+        return;
+    }
+    const int work = (blockIdx.x & 7) * per_xcd + slot - per_xcd_tall;
     if (work >= n_work) return;
     const int m_tile = work / p.n_ntiles, n_tile = work - m_tile * p.n_ntiles;
     const int4 tm = p.tile_map[m_tile];
+    if (tm.w) {
+        // a tall row block owns as many work slots as an M-tile and uses the first n_tall of them
+        if (n_tile < p.n_tall) tall_unit<MODE>(p, tm, n_tile, G0, G1, G2, G3, G4);
+        return;
+    }
     const int g = tm.x, m0 = tm.y, m_end = tm.z;
     constexpr int BN = (MODE == 0) ? 128 : 256;     // output columns per tile
     const int n0 = n_tile * BN;
@@ -306,8 +553,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         const int col = (MODE == 0) ? n0 + 32 * (j & 3) + pr : n0 + 32 * j + pr;
         c.b_off[j] = min(col, N - 1) * K + chunk;
     }
-    lds_bf16* const G0 = (lds_bf16*)g0; lds_bf16* const G1 = (lds_bf16*)g1; lds_bf16* const G2 = (lds_bf16*)g2;
-    lds_bf16* const G3 = (lds_bf16*)g3; lds_bf16* const G4 = (lds_bf16*)g4;
     issue_weights<0>(G1, 0, c);
     issue_weights<1>(G1, 0, c);
     issue_weights<0>(G3, min(BK, c.k_last), c);
@@ -517,10 +762,11 @@ hipError_t launch_grouped_gemm(int mode, bool skinny, const GemmParams& p, int m
         }
         return hipGetLastError();
     }
-    // worst-case number of M-tiles: every group may end in a partial tile
+    // worst-case number of M-tiles (every group may end in a partial tile) and of tall units (one row block per
+    // group); each list is dealt to the 8 XCDs in equal runs
     const long long max_mtiles = (max_rows + BM - 1) / BM + p.G;
-    long long blocks = max_mtiles * p.n_ntiles;
-    blocks = (blocks + 7) / 8 * 8;
+    const long long per_xcd = (max_mtiles * p.n_ntiles + 7) / 8 + ((long long)p.G * p.n_tall + 7) / 8;
+    const long long blocks = per_xcd * 8;
     if (mode == 0) hipLaunchKernelGGL(ffn_tile_kernel<0>, dim3((unsigned)blocks), dim3(256), 0, st, p);
     else hipLaunchKernelGGL(ffn_tile_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, st, p);
     return hipGetLastError();

@@ -2,51 +2,17 @@
 results, and the tolerance checks. No arithmetic of the method lives here."""
 import numpy as np
 
+from paper_2605_05899_amd.harness import DeviceLayer, bf16_dev, bf16_host  # noqa: F401  (device plumbing, re-exported)
+
 ID_GAP = 1e-5            # tokens whose k-th / (k+1)-th oracle logit gap is below this are excluded from id parity
 MAX_ERR_FRAC = 2e-2      # max|err| <= 2e-2 * max|ref|
 MEAN_REL_ERR = 5e-3      # mean|err| / mean|ref| <= 5e-3
-
-
-def bf16_dev(u16, torch):
-    return torch.from_numpy(np.ascontiguousarray(u16).view(np.int16)).cuda().view(torch.bfloat16)
-
-
-def bf16_host(t, torch):
-    u = t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
-    return (u.astype(np.uint32) << 16).view(np.float32)
 
 
 def f32_to_bf16_f32(a):
     """Round an fp32 array to bf16 precision (RNE) and widen again: used to hand oracle intermediates to a call."""
     from paper_2605_05899_amd import synth
     return synth.f32_to_bf16(np.asarray(a, dtype=np.float32))
-
-
-class DeviceLayer:
-    """Device copies of one synthetic layer plus workspace and output buffers."""
-
-    def __init__(self, inp, torch, moe, max_tokens=None):
-        self.inp, self.torch, self.moe = inp, torch, moe
-        self.cfg = moe.MoEConfig(H=inp.H, I=inp.I, E=inp.E, k=inp.k, S=inp.S, norm_topk=inp.norm_topk,
-                                 max_tokens=max_tokens if max_tokens is not None else max(inp.T, 1))
-        d = lambda a: None if a is None else bf16_dev(a, torch)
-        self.x = d(inp.x)
-        self.keep = None if inp.keep_idx is None else torch.from_numpy(inp.keep_idx).cuda()
-        self.w_router, self.w_gate, self.w_up, self.w_down = d(inp.w_router), d(inp.w_gate), d(inp.w_up), d(inp.w_down)
-        self.ws_gate, self.ws_up, self.ws_down = d(inp.ws_gate), d(inp.ws_up), d(inp.ws_down)
-        self.ws = moe.alloc_workspace(self.cfg)
-        T, k, H = inp.T, inp.k, inp.H
-        self.out = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
-        self.ids = torch.zeros((T, k), dtype=torch.int32, device="cuda")
-        self.w = torch.zeros((T, k), dtype=torch.float32, device="cuda")
-
-    def forward(self, want_routing=True):
-        i = self.inp
-        self.moe.moe_layer_forward(self.cfg, self.x, i.T_in, self.keep, i.T, self.w_router, self.w_gate, self.w_up,
-                                   self.w_down, self.ws_gate, self.ws_up, self.ws_down, self.out,
-                                   self.ids if want_routing else None, self.w if want_routing else None, self.ws)
-        self.torch.cuda.synchronize()
-        return bf16_host(self.out, self.torch), self.ids.cpu().numpy(), self.w.cpu().numpy()
 
 
 def oracle_layer(inp, dtype=np.float32):

@@ -42,6 +42,11 @@ SMALL = [
     (115, 40, 128, 128, 64, 64, 0, None, 4),      # k at its maximum (64 of 128 experts per token)
     (116, 50, 128, 8, 2, 64, 8, None, 5),         # S at its maximum (8 shared experts)
     (117, 2100, 64, 3, 3, 64, 0, None, 100),      # smallest H and I, 2100 rows per expert (9 M-tiles each)
+    # many small groups (mean 94 rows): groups of at most 128 rows run as tall units next to the M-tiles of the larger
+    # ones; I = 256 + 192 and H = 512 + 320 leave the last tall unit ragged in both GEMMs (idle and half-used waves)
+    (118, 6000, 832, 128, 2, 448, 0, None, 600),
+    # the same with a retained-index list and a shared expert (one 2600-row group of M-tiles among 128 small groups)
+    (119, 4000, 1024, 128, 3, 512, 1, 2300, 300),
 ]
 
 
