@@ -318,6 +318,51 @@ def measure_expert_cache():
             "predict_host_us_per_expert": min(a[1] for a in alone), "acquire_host_us_8_hits": min(a[2] for a in alone)}
 
 
+def measure_prefetch_pipeline():
+    """Compute-stream stall per layer of a four-layer stack in decode steps (4 tokens, 64 experts, top-4, slabs of
+    9.4 MB like the C4 model's experts) whose experts live in pinned host memory behind a cache of 160 slabs (of 256
+    experts), for three sources of the lookahead list (paper Sec. 3.4.2): none (every absent expert fetched on demand),
+    the library's predictor MLP with random weights (a list no better than chance), and a stand-in that names the
+    next layer's true experts with recall 0.9. Every step routes a fresh token batch, so the set of experts a layer
+    needs drifts from step to step; four steps fill the cache, sixteen are measured."""
+    import numpy as np
+    import torch
+    from paper_2605_05899_amd import harness, moe, pipeline, synth
+
+    n_layers, T, H, E, k, I, n_slabs, budget, n_warm, n_steps = 4, 4, 2048, 64, 4, 768, 160, 14, 4, 16
+    layers = [synth.make_small(900 + l, T, H, E, k, I, 0) for l in range(n_layers)]
+    rng_x = np.random.default_rng(13)
+    batches = [[harness.bf16_dev(synth.f32_to_bf16(rng_x.standard_normal((T, H)).astype(np.float32)), torch)
+                for _ in range(n_layers)] for _ in range(n_warm + n_steps)]
+    out = {"shape": {"layers": n_layers, "T": T, "H": H, "E": E, "k": k, "I": I, "slab_MB": 3 * I * H * 2 / 1e6,
+                     "n_slabs": n_slabs, "list_length": budget, "warm_steps": n_warm, "steps": n_steps}}
+    for name, mode, recall in (("demand_only", "demand", 0.0), ("mlp_random_weights", "mlp", 0.0),
+                               ("standin_recall_0.9", "standin", 0.9)):
+        stack = pipeline.CachedLayerStack(torch, moe, layers, n_slabs=n_slabs, budget=budget)
+        try:
+            if mode == "mlp":
+                stack.set_random_mlp(11)
+            rng = np.random.default_rng(12)
+            stats, per_layer = pipeline.StackStats(), []
+            for i, xs in enumerate(batches):
+                stack.x = xs
+                truth = stack.true_experts()
+                if i == n_warm:
+                    stats, before = pipeline.StackStats(), stack.cache.stats()
+                if i >= n_warm:
+                    per_layer += [len(t) for t in truth]
+                stack.run_pass(mode, stats, truth=truth, recall=recall, rng=rng)
+            after = stack.cache.stats()
+            s = stats.summary({kk: after[kk] - before[kk] for kk in after})
+            out[name] = {kk: s[kk] for kk in ("stall_us_mean", "stall_us_max", "experts_demanded", "demand_misses",
+                                              "experts_listed", "prefetch_copies_started", "cache_hits",
+                                              "cache_evictions", "cache_refused", "wall_ms")}
+            out[name]["experts_per_layer_mean"] = float(np.mean(per_layer))
+        finally:
+            stack.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -403,6 +448,7 @@ def main():
                                                                             not a.no_cpu_baseline)
         line["also"]["predictor_features"] = measure_predictor_features(max(a.steps, 200), a.warmup)
         line["also"]["expert_cache"] = measure_expert_cache()
+        line["also"]["expert_cache"]["prefetch_pipeline"] = measure_prefetch_pipeline()
     print(json.dumps(line))
 
 

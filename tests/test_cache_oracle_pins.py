@@ -109,3 +109,84 @@ def test_demand_with_nothing_evictable_fails_loudly():
     m.predict([(0, 0, 0.5), (0, 1, 0.4)])
     with pytest.raises(CO.CacheFull):
         m.acquire(0, [2])                      # both slabs hold Required experts of a layer that has not run
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# Brute force over a flat event log: every eviction the model makes is checked against the classes and priorities
+# that follow, expert by expert, from the plain sequence of calls (readings K1-K7), not from the model's own tables.
+def _state_at(events, key, upto):
+    """(resident, class, priority) of one expert after events[:upto], by replaying only what concerns it."""
+    resident, cls, prio = False, None, None
+    for ev in events[:upto]:
+        kind = ev[0]
+        if kind == "fetch" and ev[1] == key:
+            resident, cls, prio = True, CO.REQUIRED, ev[2]
+        elif kind == "evict" and ev[1] == key:
+            resident, cls, prio = False, None, None
+        elif not resident:
+            continue
+        elif kind == "predict" and cls == CO.REQUIRED and key not in ev[1]:
+            cls = CO.SPECULATIVE                    # dropped by a newer list before its layer ran: still protected
+        elif kind == "listed" and ev[1] == key:
+            cls, prio = CO.REQUIRED, ev[2]
+        elif kind == "demanded" and ev[1] == key:
+            cls = CO.REQUIRED
+        elif kind == "done" and ev[1] == key[0]:
+            cls = CO.EXPIRED
+    return resident, cls, prio
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_every_eviction_takes_the_least_valuable_expired_expert_brute_force(seed):
+    n_slabs, n_layers, E = 16, 4, 12
+    m = CO.ExpertCacheModel(n_slabs)
+    events, n_evictions, n_refused = [], 0, 0
+    all_keys = [(l, e) for l in range(n_layers) for e in range(E)]
+
+    def absorb_fetches(n_log_before, prio_of):
+        nonlocal n_evictions
+        for what, key, victim in m.log[n_log_before:]:
+            states = {k: _state_at(events, k, len(events)) for k in all_keys}
+            residents = [k for k, s in states.items() if s[0]]
+            assert not states[key][0], "fetched an expert that was resident"
+            if victim is None:
+                assert len(residents) < n_slabs, "took a free slab when none was free"
+            else:
+                n_evictions += 1
+                assert len(residents) == n_slabs, "evicted although a slab was free"
+                assert states[victim][0] and states[victim][1] == CO.EXPIRED, "evicted a protected expert"
+                expired = [(states[k][2], k) for k in residents if states[k][1] == CO.EXPIRED]
+                assert (states[victim][2], victim) == min(expired), "a less valuable expired expert was resident"
+                events.append(("evict", victim))
+            events.append(("fetch", key, prio_of(key)))
+
+    for op in random_trace(seed, n_layers=n_layers, E=E, passes=4):
+        n_log = len(m.log)
+        if op[0] == "predict":
+            listed = {(l, e): p for l, e, p in op[1]}
+            events.append(("predict", set(listed)))
+            for k, p in listed.items():
+                events.append(("listed", k, p))
+            refused_before = m.stats["refused"]
+            m.predict(op[1])
+            absorb_fetches(n_log, lambda k: listed[k])
+            if m.stats["refused"] > refused_before:
+                n_refused += m.stats["refused"] - refused_before
+                states = {k: _state_at(events, k, len(events)) for k in all_keys}
+                assert sum(s[0] for s in states.values()) == n_slabs
+                assert not any(s[0] and s[1] == CO.EXPIRED for s in states.values()), "refused although evictable"
+        elif op[0] == "acquire":
+            for e in sorted(set(op[2])):
+                events.append(("demanded", (op[1], e)))
+            m.acquire(op[1], op[2])
+            absorb_fetches(n_log, lambda k: 0.0)
+        elif op[0] == "layer_done":
+            m.layer_done(op[1])
+            events.append(("done", op[1]))
+        # the model's tables must agree with the flat reconstruction after every call
+        for k in all_keys:
+            res, cls, prio = _state_at(events, k, len(events))
+            assert res == (k in m.slab_of)
+            if res:
+                assert (cls, prio) == (m.cls[k], m.prio[k]), (op[0], k)
+    assert n_evictions > 20          # the traces do exercise eviction
