@@ -191,7 +191,7 @@ hipError_t run_ffn(const moe_config& c, const bf16_t* x, const int* keep_idx, in
     p.B0 = w_down; p.B1 = nullptr; p.Bs0 = ws_down; p.Bs1 = nullptr;
     p.C = y; p.ldc = c.H; p.K = c.I; p.N = c.H;
     p.n_ntiles = (c.H + 255) / 256;
-    p.n_tall = (c.H + 511) / 512;
+    p.n_tall = (c.H + 255) / 256;
     timer_mark(3, 0, st);
     e = launch_grouped_gemm(1, skinny, p, rows, st);
     timer_mark(3, 1, st);

@@ -159,7 +159,7 @@ __device__ __forceinline__ void slab_step(lds_bf16* __restrict__ ca, lds_bf16* _
 
 // Epilogue of a wave's 128 x 128 sub-tile: lane = token r of fragment t; registers i = output columns 16*q + i of
 // fragment j. MODE 0 applies SwiGLU to the gate (j = 0, 1) and up (j = 2, 3) sums of the same columns.
-template <int MODE, int NT>
+template <int MODE, int NT, int NJ = 4>
 __device__ __forceinline__ void store_acc(const GemmParams& p, const floatx16 (&acc)[4][4], int m_first, int m_end,
                                           int n_first, int q) {
     const int r = threadIdx.x & 31;
@@ -185,7 +185,7 @@ __device__ __forceinline__ void store_acc(const GemmParams& p, const floatx16 (&
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < NJ; ++j) {
                 const int col = n_first + j * 32 + 16 * q;
                 if (col >= p.N) continue;
                 uint32_t o[8];
@@ -247,11 +247,11 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const TileCtx& c,
 
 // ---------------------------------------------------------------------------------------------- tall work units
 // A group of at most kTallM = 128 rows would fill an M-tile less than half while its workgroups still stream a full
-// tile's weight rows. Such groups are computed as tall units instead: 128 tokens against
-// 512 weight rows (MODE 0: 256 gate + 256 up rows = 256 output columns; MODE 1: 512 output columns), half as many
-// workgroups per group, each weight row still read once, the token rows read half as often. The four waves sit
-// side by side: every wave multiplies all 128 tokens with its own 128 weight rows, i.e. the same 4 x 4 fragments per
-// wave as in an M-tile. A wave's weight rows are its private business (it requests them and is the only one to
+// tile's weight rows. Such groups are computed as tall units instead: 128 tokens against 256 output columns (MODE 0:
+// 256 gate + 256 up weight rows, half as many workgroups per group as M-tiles, the token rows read half as often;
+// MODE 1: 256 down rows, as many workgroups as M-tiles but without the dead half of the token tile), each weight row
+// still read once. The four waves sit side by side: every wave multiplies all 128 tokens with its own weight rows
+// (MODE 0: 64 gate + 64 up, the same 4 x 4 fragments per wave as in an M-tile; MODE 1: 64 down rows, 4 x 2). A wave's weight rows are its private business (it requests them and is the only one to
 // read them), the token rows are shared. LDS = ten 16 KB blocks: tokens of the slab being multiplied and of the next
 // one, and per wave its weight rows of the two slabs. One barrier per slab: behind it every wave has finished with
 // the current blocks and the next slab has landed, so the blocks just freed are requested again at once (slab i + 2)
@@ -273,30 +273,33 @@ __device__ __forceinline__ void tall_issue_tokens(lds_bf16* __restrict__ tok, in
     for (int j = 0; j < 4; ++j)
         __builtin_amdgcn_global_load_lds((gptr_t)(c.a_base + c.a_off[j] + k0), (lptr_t)(tok + c.tok_blk + j * 512), 16, 0, 0);
 }
+// NJ = weight fragments per wave: 4 in MODE 0 (64 gate + 64 up rows), 2 in MODE 1 (64 down rows).
+template <int NJ>
 __device__ __forceinline__ void tall_issue_weights(lds_bf16* __restrict__ wts, int k0, const TallCtx& c) {
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
-        __builtin_amdgcn_global_load_lds((gptr_t)(c.b_base[j >> 3] + c.b_off[j] + k0), (lptr_t)(wts + j * 512), 16, 0, 0);
+    for (int j = 0; j < 4 * NJ; ++j)
+        __builtin_amdgcn_global_load_lds((gptr_t)(c.b_base[j / (2 * NJ)] + c.b_off[j] + k0), (lptr_t)(wts + j * 512), 16, 0,
+                                         0);
 }
 
-// Half of the MFMAs of a k-step (token fragments [HALF NT/2, (HALF+1) NT/2)).
-template <int NT, int HALF>
-__device__ __forceinline__ void mma_half(const Frags& f, floatx16 (&acc)[4][4]) {
+// The MFMAs of token fragments [T0, T1) of a k-step.
+template <int T0, int T1, int NJ>
+__device__ __forceinline__ void mma_tall(const Frags& f, floatx16 (&acc)[4][4]) {
 #pragma unroll
-    for (int t = HALF * NT / 2; t < (HALF + 1) * NT / 2; ++t)
+    for (int t = T0; t < T1; ++t)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NJ; ++j)
             acc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.w[j], f.x[t], acc[t][j], 0, 0, 0);
 }
 
-template <int NT>
+template <int NT, int NJ>
 __device__ __forceinline__ void tall_read(const lds_bf16* __restrict__ tok, const lds_bf16* __restrict__ wts, int ks,
                                           const TallCtx& c, Frags& f) {
     const int ch = ((ks * 2 + c.q) ^ c.key) * 8;
 #pragma unroll
     for (int t = 0; t < NT; ++t) f.x[t] = *reinterpret_cast<lds_frag_ptr>(tok + c.a_row + t * 32 * BK + ch);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) f.w[j] = *reinterpret_cast<lds_frag_ptr>(wts + c.b_row[j] + ch);
+    for (int j = 0; j < NJ; ++j) f.w[j] = *reinterpret_cast<lds_frag_ptr>(wts + c.b_row[j] + ch);
 }
 
 // Instruction order of a tall k-step (or half of one): MFMAs with `reads` fragment reads and `loads` direct-to-LDS
@@ -318,41 +321,42 @@ __device__ __forceinline__ void pin_tall() {
 // The wave's own weight block is requested again (slab i + 2) as soon as the wave has read its last fragments from
 // it, before the barrier, so that loads are in flight while the waves wait for each other; the token block is shared
 // and follows behind the barrier.
-template <int NT>
+template <int NT, int NJ>
 __device__ __forceinline__ void tall_step(lds_bf16* __restrict__ tc, lds_bf16* __restrict__ wc, lds_bf16* __restrict__ tn,
                                           lds_bf16* __restrict__ wn, int k2, const TallCtx& c, Frags& f0, Frags& f1,
                                           floatx16 (&acc)[4][4]) {
-    if (NT > 0) tall_read<NT>(tc, wc, 1, c, f1);
-    mma_step<NT>(f0, acc);
-    pin_tall<4 * NT, 4 + NT, 0>();
+    if (NT > 0) tall_read<NT, NJ>(tc, wc, 1, c, f1);
+    mma_tall<0, NT, NJ>(f0, acc);
+    pin_tall<NJ * NT, NJ + NT, 0>();
     __builtin_amdgcn_sched_barrier(0);
-    if (NT > 0) tall_read<NT>(tc, wc, 2, c, f0);
-    mma_step<NT>(f1, acc);
-    pin_tall<4 * NT, 4 + NT, 0>();
+    if (NT > 0) tall_read<NT, NJ>(tc, wc, 2, c, f0);
+    mma_tall<0, NT, NJ>(f1, acc);
+    pin_tall<NJ * NT, NJ + NT, 0>();
     __builtin_amdgcn_sched_barrier(0);
-    if (NT > 0) tall_read<NT>(tc, wc, 3, c, f1);
-    mma_half<NT, 0>(f0, acc);
-    pin_tall<2 * NT, 4 + NT, 0>();
+    if (NT > 0) tall_read<NT, NJ>(tc, wc, 3, c, f1);
+    mma_tall<0, NT / 2, NJ>(f0, acc);
+    pin_tall<NJ * NT / 2, NJ + NT, 0>();
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): this wave's reads of wc have returned
-    tall_issue_weights(wc, k2, c);
-    mma_half<NT, 1>(f0, acc);
-    pin_tall<2 * NT, 0, 16>();
+    tall_issue_weights<NJ>(wc, k2, c);
+    mma_tall<NT / 2, NT, NJ>(f0, acc);
+    pin_tall<NJ * NT / 2, 0, 4 * NJ>();
     __builtin_amdgcn_sched_barrier(0);
-    // slab i + 1 has landed (this wave's share): all loads but the 16 just issued: vmcnt(16)
-    __builtin_amdgcn_s_waitcnt(0x4F70);
+    // slab i + 1 has landed (this wave's share): all loads but the 4 NJ just issued
+    __builtin_amdgcn_s_waitcnt(NJ == 4 ? 0x4F70 : 0x0F78);      // vmcnt(16) / vmcnt(8)
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     tall_issue_tokens(tc, k2, c);
-    if (NT > 0) tall_read<NT>(tn, wn, 0, c, f0);
-    mma_step<NT>(f1, acc);
-    pin_tall<4 * NT, 4 + NT, 4>();
+    if (NT > 0) tall_read<NT, NJ>(tn, wn, 0, c, f0);
+    mma_tall<0, NT, NJ>(f1, acc);
+    pin_tall<NJ * NT, NJ + NT, 4>();
     __builtin_amdgcn_sched_barrier(0);
 }
 
 template <int MODE, int NT>
 __device__ __forceinline__ void tall_body(const GemmParams& p, const TallCtx& c, lds_bf16* T0, lds_bf16* T1, lds_bf16* W0,
                                           lds_bf16* W1, int m0, int m_end, int n_first) {
+    constexpr int NJ = (MODE == 0) ? 4 : 2;
     floatx16 acc[4][4];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
@@ -365,21 +369,22 @@ __device__ __forceinline__ void tall_body(const GemmParams& p, const TallCtx& c,
     // every step requests one slab (past the end of K the last one again), so the loads in flight behind a wait are
     // the same on every path
     tall_issue_tokens(T0, 0, c);
-    tall_issue_weights(W0, 0, c);
+    tall_issue_weights<NJ>(W0, 0, c);
     tall_issue_tokens(T1, slab_k(1), c);
-    tall_issue_weights(W1, slab_k(1), c);
-    __builtin_amdgcn_s_waitcnt(0x4070 | 4);      // vmcnt(20): slab 0 has landed, slab 1 may be in flight
+    tall_issue_weights<NJ>(W1, slab_k(1), c);
+    // slab 0 has landed, slab 1 (4 + 4 NJ loads) may be in flight: vmcnt(20) / vmcnt(12)
+    __builtin_amdgcn_s_waitcnt(NJ == 4 ? 0x4074 : 0x007C);
     __builtin_amdgcn_s_barrier();
     Frags f0, f1;
-    if (NT > 0) tall_read<NT>(T0, W0, 0, c, f0);
+    if (NT > 0) tall_read<NT, NJ>(T0, W0, 0, c, f0);
     int i = 0;
     for (; i + 2 <= KT; i += 2) {
-        tall_step<NT>(T0, W0, T1, W1, slab_k(i + 2), c, f0, f1, acc);
-        tall_step<NT>(T1, W1, T0, W0, slab_k(i + 3), c, f0, f1, acc);
+        tall_step<NT, NJ>(T0, W0, T1, W1, slab_k(i + 2), c, f0, f1, acc);
+        tall_step<NT, NJ>(T1, W1, T0, W0, slab_k(i + 3), c, f0, f1, acc);
     }
-    if (i < KT) tall_step<NT>(T0, W0, T1, W1, slab_k(i + 2), c, f0, f1, acc);
+    if (i < KT) tall_step<NT, NJ>(T0, W0, T1, W1, slab_k(i + 2), c, f0, f1, acc);
     __builtin_amdgcn_s_waitcnt(0x0070);      // no load may still be writing LDS when the workgroup releases it
-    store_acc<MODE, NT>(p, acc, m0, m_end, n_first, c.q);
+    store_acc<MODE, NT, NJ>(p, acc, m0, m_end, n_first, c.q);
 }
 
 template <int MODE>
@@ -398,8 +403,9 @@ __device__ __forceinline__ void tall_unit(const GemmParams& p, const int4 tm, in
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, q = lane >> 5;
     const int g = tm.x, m0 = tm.y, m_end = tm.z;            // 1 <= m_end - m0 <= kTallM
-    constexpr int BNU = (MODE == 0) ? 256 : 512;            // output columns per unit
-    constexpr int BNW = BNU / 4;                            // ... per wave
+    constexpr int BNU = 256;                                // output columns per unit
+    constexpr int BNW = BNU / 4;                            // ... per wave: 64 (MODE 0: 64 gate + 64 up weight rows)
+    constexpr int NJ = (MODE == 0) ? 4 : 2;                 // weight fragments per wave
     const int n0 = n_unit * BNU;
     const int K = p.K, N = p.N;
     const bf16_t *b0, *b1;
@@ -424,10 +430,10 @@ __device__ __forceinline__ void tall_unit(const GemmParams& p, const int4 tm, in
     const int n_first = n0 + wave * BNW;                    // first output column of this wave
     // weight rows of the wave's private block: block row m = 32 f + rr holds, for fragment f,
     //   MODE 0: f = 0, 1 gate rows and f = 2, 3 up rows of output columns n_first + 32 (f & 1) + frag_perm(rr)
-    //   MODE 1: down rows n_first + 32 f + frag_perm(rr)
+    //   MODE 1: f = 0, 1 down rows n_first + 32 f + frag_perm(rr)
     // Columns past N are clamped and never stored.
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
+    for (int j = 0; j < 4 * NJ; ++j) {
         const int rr = 8 * (j & 3) + lrow, f = j >> 2;
         const int chunk = (lpos ^ ((rr >> 1) & 7)) * 8;
         const int col = (MODE == 0) ? n_first + 32 * (f & 1) + frag_perm(rr) : n_first + 32 * f + frag_perm(rr);
@@ -447,7 +453,7 @@ __device__ __forceinline__ void tall_unit(const GemmParams& p, const int4 tm, in
     }
     c.a_row = r * BK;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) c.b_row[j] = (32 * j + r) * BK;
+    for (int j = 0; j < NJ; ++j) c.b_row[j] = (32 * j + r) * BK;
     // LDS blocks. The compiler lets a fragment read overtake the loads in flight only when it can tell that they
     // touch different __shared__ arrays, so for every wave the blocks of one slab parity (tokens and its weights) and
     // those of the other parity must lie in different arrays, with pointers that are constants of the code path:
