@@ -1,12 +1,13 @@
 #!/bin/bash
 # Runs on a GPU machine from the repository root: the rocprofv3 passes behind the summaries kept under profiles/.
-# Every rocprofv3 line runs committed files only (bench.py and the built library). Raw output goes to
-# gpurun_out/prof; `python -m paper_2605_05899_amd.profile_summary regen gpurun_out/prof` turns it into profiles/.
+# Every rocprofv3 line runs committed files only (bench.py and the built library). Raw output goes to the directory
+# named by PROF_OUT (default prof_raw under the repository root);
+# `python -m paper_2605_05899_amd.profile_summary regen <that directory>` turns it into profiles/.
 # Counters are collected in runs of their own (one counter block per run, no tracing alongside).
 set -o pipefail
 R=${GRAFT_REPO_ROOT:-$(pwd)}
 cd /tmp && export TMPDIR=/tmp
-O=$R/gpurun_out/prof; rm -rf $O; mkdir -p $O
+O=${PROF_OUT:-$R/prof_raw}; case $O in /*) ;; *) O=$R/$O;; esac; rm -rf $O; mkdir -p $O
 for W in ${WORKLOADS:-C4 C5 C3}; do
   B="python3 $R/bench.py --config $W --no-cpu-baseline --no-also"
   timeout -s KILL 300 rocprofv3 --kernel-trace --stats -d $O/${W}_trace -o t --output-format csv -- $B --steps 50 --warmup 10 > $O/${W}_trace.log 2>&1 || exit 1

@@ -3,7 +3,7 @@
     python -m paper_2605_05899_amd.profile_summary stats  <..._kernel_stats.csv>
     python -m paper_2605_05899_amd.profile_summary pmc    <..._counter_collection.csv> [more csv ...]
     python -m paper_2605_05899_amd.profile_summary traffic <workload> <fetch csv> <write csv>
-    python -m paper_2605_05899_amd.profile_summary regen   <raw dir>     (default gpurun_out/prof)
+    python -m paper_2605_05899_amd.profile_summary regen   <raw dir>
 
 `regen` rebuilds every file under profiles/ from the raw output of paper_2605_05899_amd/collect_profiles.sh (run on a
 GPU machine) and stamps profiles/hbm_traffic.json with the commit of the tree it is run on.
@@ -102,7 +102,7 @@ SQ_COUNTERS = ("SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_
 TCC_COUNTERS = "TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum GRBM_GUI_ACTIVE"
 
 
-def regen(raw="gpurun_out/prof", out_dir="profiles"):
+def regen(raw, out_dir="profiles"):
     """profiles/*.txt and profiles/hbm_traffic.json from the raw rocprofv3 output of collect_profiles.sh."""
     import contextlib
     import io
@@ -175,8 +175,8 @@ def regen(raw="gpurun_out/prof", out_dir="profiles"):
 
 
 if __name__ == "__main__":
-    if len(sys.argv) >= 2 and sys.argv[1] == "regen":
-        regen(*(sys.argv[2:3] or ["gpurun_out/prof"]))
+    if len(sys.argv) >= 3 and sys.argv[1] == "regen":
+        regen(sys.argv[2])
         sys.exit(0)
     if len(sys.argv) < 3 or sys.argv[1] not in ("stats", "pmc", "traffic"):
         sys.exit(__doc__)
