@@ -535,6 +535,8 @@ moe_status moe_token_compress(const float* attn, int32_t n_heads, int32_t N, con
                       "token_compress");
 }
 
+int32_t moe_compress_wide_min_tokens(int32_t n) { return compress_wide_min_tokens(n); }
+
 size_t moe_mean_pool_workspace_bytes(int32_t D) {
     if (D < 8 || D % 8 != 0) return 0;
     return mean_pool_workspace_bytes(D);

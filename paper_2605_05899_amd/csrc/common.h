@@ -166,6 +166,7 @@ hipError_t launch_combine(const bf16_t* y, const int* inv_perm, const float* top
                           const bf16_t* extra, int n_extra, long long extra_stride, bf16_t* out, hipStream_t st);
 
 size_t compress_workspace_bytes(int N, int E);
+int compress_wide_min_tokens(int n);
 hipError_t launch_token_compress(const float* attn, int n_heads, int N, const int* ids, int L, int k, int E, int K_core,
                                  int K_keep, float lambda, int* keep_idx, float* s_norm_out, float* delta_out, void* ws,
                                  hipStream_t st);

@@ -29,7 +29,7 @@ EXPORTS = ("moe_workspace_bytes", "moe_status_string", "moe_route", "moe_dispatc
            "moe_mean_pool", "moe_routing_histogram", "moe_lookahead_target", "moe_cache_create", "moe_cache_destroy",
            "moe_cache_predict", "moe_cache_acquire", "moe_cache_layer_done", "moe_cache_query", "moe_cache_stats",
            "moe_predictor_workspace_bytes", "moe_predictor_forward", "moe_index_checks_enable",
-           "moe_static_scratch_bytes", "moe_layer_forward_static")
+           "moe_static_scratch_bytes", "moe_layer_forward_static", "moe_compress_wide_min_tokens")
 N_STAGES = 5
 STAGE_NAMES = ("route", "dispatch", "gate_up_swiglu", "down", "combine")
 
@@ -83,6 +83,8 @@ _lib.moe_layer_forward_static.restype = ctypes.c_int
 _lib.moe_layer_forward_static.argtypes = [_CFG, _P, _I32, _P, _I32] + [_P] * 11
 _lib.moe_static_scratch_bytes.restype = ctypes.c_size_t
 _lib.moe_static_scratch_bytes.argtypes = []
+_lib.moe_compress_wide_min_tokens.restype = ctypes.c_int32
+_lib.moe_compress_wide_min_tokens.argtypes = [_I32]
 _lib.moe_compress_workspace_bytes.restype = ctypes.c_size_t
 _lib.moe_compress_workspace_bytes.argtypes = [_I32, _I32]
 _lib.moe_token_compress.restype = ctypes.c_int
@@ -239,6 +241,10 @@ def moe_token_compress(attn, n_heads, N, prefix_topk_ids, L, k, E, alpha, beta, 
     st = _lib.moe_token_compress(_ptr(attn), n_heads, N, _ptr(prefix_topk_ids), L, k, E, float(alpha), float(beta),
                                  float(lam), _ptr(keep_idx), _ptr(s_norm), _ptr(delta), _ptr(ws), _stream(stream))
     return _check(st, "moe_token_compress", check)
+
+
+def moe_compress_wide_min_tokens(n: int) -> int:
+    return int(_lib.moe_compress_wide_min_tokens(int(n)))
 
 
 def moe_mean_pool_workspace_bytes(D: int) -> int:

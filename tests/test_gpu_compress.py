@@ -74,10 +74,44 @@ def test_small_cases(env, case):
         check(torch, moe, c, alpha, beta, lam)
 
 
-@pytest.mark.parametrize("name", ["P1", "P2"])
+@pytest.fixture
+def wide_path(env):
+    """Forces the many-workgroup code path for every token count (it is otherwise taken from about 12 K tokens on)."""
+    _, moe = env
+    before = moe.moe_compress_wide_min_tokens(0)
+    yield
+    moe.moe_compress_wide_min_tokens(before)
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[f"seed{c[0]}" for c in SMALL])
+def test_small_cases_wide_path(env, wide_path, case):
+    torch, moe = env
+    seed, N, heads, E, L, k = case
+    c = synth.make_compress_small(seed, N=N, n_heads=heads, E=E, L=L, k=min(k, E), n_clusters=4)
+    for alpha, beta, lam in [(0.1, 0.25, 2.0), (0.0, 0.5, 2.0), (0.3, 0.3, 2.0), (0.05, 1.0, 0.5), (0.5, 0.9, 1e6)]:
+        check(torch, moe, c, alpha, beta, lam, label=f"{c.name} (wide path)")
+
+
+@pytest.mark.parametrize("name", ["P1", "P2", "P3"])
 def test_workloads_full_size(env, name):
     torch, moe = env
     check(torch, moe, synth.make_compress_config(name))
+
+
+@pytest.mark.parametrize("name", ["P1", "P2"])
+def test_workloads_full_size_wide_path(env, wide_path, name):
+    torch, moe = env
+    check(torch, moe, synth.make_compress_config(name), label=f"{name} (wide path)")
+
+
+def test_threshold_setter(env):
+    _, moe = env
+    default = moe.moe_compress_wide_min_tokens(-1)
+    assert default > 0
+    assert moe.moe_compress_wide_min_tokens(5) == default
+    assert moe.moe_compress_wide_min_tokens(-1) == 5
+    assert moe.moe_compress_wide_min_tokens(default) == 5
+    assert moe.moe_compress_wide_min_tokens(-1) == default
 
 
 def test_long_video_sampled(env):
@@ -105,6 +139,23 @@ def test_long_video_sampled(env):
     order = outside[np.lexsort((outside, -p[outside].astype(np.float64)))]
     extra = order[: len(keep) - K_core]
     np.testing.assert_array_equal(np.sort(np.concatenate([core, extra])), keep)
+
+
+def test_ties_wide_path(env, wide_path):
+    """Few distinct saliency values over many tokens: both selections end inside a run of equal keys that spans
+    several workgroups, so the rank among equal keys in token order decides."""
+    torch, moe = env
+    rng = np.random.default_rng(7)
+    N = 3000
+    A = rng.integers(0, 4, size=(1, N)).astype(np.float32)
+    R = rng.integers(0, 16, size=(2, N, 2)).astype(np.int32)
+    R[:, N // 2:, :] = 3                       # half of the tokens share one expert set: equal scores
+    for alpha, beta in [(0.1, 0.4), (0.26, 0.7), (0.0, 0.33), (0.5, 0.5)]:
+        want = CO.token_compress(A, R, 16, alpha, beta, 2.0)
+        keep, s_norm, delta = run_gpu(torch, moe, A, R, 16, alpha, beta, 2.0)
+        np.testing.assert_array_equal(keep, want["I_keep"])
+        np.testing.assert_array_equal(delta, want["delta"])
+    test_ties_constant_saliency_and_bad_ids(env)
 
 
 def test_ties_constant_saliency_and_bad_ids(env):
