@@ -3,9 +3,9 @@
 // keeps ascending token order, which makes the permutation a pure function of the routing decision. So there is
 // no arrival-order atomic anywhere: ranks come from wave ballots, per-wave counters in LDS and prefix sums.
 //
-// Large inputs: rank kernel (one workgroup per kDispChunk assignments) -> scan kernel (one workgroup) -> scatter
-// kernel. Small inputs (T*k <= 8192): one workgroup does all three steps.
-// The scan step also emits the M-tile map of the tiled grouped GEMM and appends one group per shared expert
+// Large inputs: rank kernel (one workgroup per kDispChunk assignments) -> scatter kernel (prefix over chunks and
+// experts recomputed by every workgroup, then the positions). Small inputs (T*k <= 8192): one workgroup does it all.
+// The scatter step also emits the M-tile map of the tiled grouped GEMM and appends one group per shared expert
 // (every token, identity order) behind the routed groups.
 #include "common.h"
 #include "topk.h"
@@ -289,46 +289,76 @@ __global__ __launch_bounds__(256) void dispatch_rank_kernel(const int* __restric
     }
 }
 
-// Step 2: per expert, exclusive prefix of the chunk histograms over chunks (in place); then offsets + tile map.
-__global__ __launch_bounds__(1024) void dispatch_scan_kernel(int* __restrict__ hist, int n_chunks, int T, int E, int S,
-                                                             int tall_rows,
-                                                             int* __restrict__ offsets, int* __restrict__ n_tiles,
-                                                             int4* __restrict__ tile_map) {
+// Step 2: final positions. One workgroup per chunk (and the same 1024 assignments). Every workgroup first adds up,
+// per expert, the histograms of all chunks (the group sizes) and of the chunks before its own (where its chunk's
+// rows start inside each group): chunks are dealt to 1024 / E_pad thread groups whose partial sums meet in LDS, so a
+// workgroup reads the whole chunk x expert table once, from L2, in a batch or two of independent loads. A scan over
+// the group sizes gives the group offsets. That is redundant work in every workgroup and still cheaper than a
+// launch of its own for the scan: the table is small and a launch costs microseconds. Workgroup 0 also writes the
+// offsets and the tile map; the identity rows of the shared-expert groups are spread over all workgroups.
+__global__ __launch_bounds__(1024) void dispatch_scatter_kernel(const int* __restrict__ ids, int T, int k, int E, int S,
+                                                                int e_pad, int tall_rows, const int* __restrict__ hist,
+                                                                int n_chunks, int* __restrict__ offsets,
+                                                                int* __restrict__ n_tiles, int4* __restrict__ tile_map,
+                                                                int* __restrict__ sorted_token,
+                                                                int* __restrict__ inv_perm /* in: rank, out: position */) {
     __shared__ int s_scan[1024];
+    __shared__ int s_part[2][1024];          // [total | before][thread group * e_pad + expert]
+    __shared__ int s_base[kMaxE];            // group offset + rows of the earlier chunks, per expert
     const int tid = threadIdx.x;
-    int total = 0;
-    if (tid < E) {
-        for (int b0 = 0; b0 < n_chunks; b0 += 16) {       // 16 loads in flight, then their prefix in chunk order
-            int c[16];
+    const int N = T * k, G = E + S;
+    const int parts = 1024 / e_pad;          // e_pad: E rounded up to a power of two (at most 512): at least 2 groups
+    {
+        const int e = tid & (e_pad - 1), part = tid / e_pad;
+        int tot = 0, before = 0;
+        if (e < E) {
+            for (int c0 = part; c0 < n_chunks; c0 += 16 * parts) {
+                int h[16];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) c[u] = (b0 + u < n_chunks) ? hist[(size_t)(b0 + u) * E + tid] : 0;
+                for (int u = 0; u < 16; ++u) {
+                    const int c = c0 + u * parts;
+                    h[u] = (c < n_chunks) ? hist[(size_t)c * E + e] : 0;
+                }
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                if (b0 + u < n_chunks) hist[(size_t)(b0 + u) * E + tid] = total;
-                total += c[u];
+                for (int u = 0; u < 16; ++u) {
+                    tot += h[u];
+                    if (c0 + u * parts < (int)blockIdx.x) before += h[u];
+                }
             }
         }
+        s_part[0][tid] = tot;
+        s_part[1][tid] = before;
     }
-    const int my_count = (tid < E) ? total : T;
-    emit_offsets_and_tiles(my_count, E + S, tall_rows, s_scan, offsets, n_tiles, tile_map, nullptr);
-}
-
-// Step 3: final positions.
-__global__ __launch_bounds__(256) void dispatch_scatter_kernel(const int* __restrict__ ids, int T, int k, int E, int S,
-                                                               const int* __restrict__ offsets,
-                                                               const int* __restrict__ hist,
-                                                               int* __restrict__ sorted_token,
-                                                               int* __restrict__ inv_perm /* in: rank, out: position */) {
-    const int N = T * k;
-    const int idx = blockIdx.x * 256 + threadIdx.x;
+    __syncthreads();
+    int my_count = 0, my_before = 0;
+    if (tid < E) {
+        for (int q = 0; q < parts; ++q) {
+            my_count += s_part[0][q * e_pad + tid];
+            my_before += s_part[1][q * e_pad + tid];
+        }
+    } else if (tid < G) {
+        my_count = T;                        // shared groups hold every token
+    }
+    const int inc = block_inclusive_scan(my_count, s_scan, tid, G);
+    const int off = inc - my_count;
+    if (tid < E) s_base[tid] = off + my_before;
+    if (blockIdx.x == 0) {
+        if (tid < G) {
+            offsets[tid] = off;
+            if (tid == G - 1) offsets[G] = inc;
+        }
+        __syncthreads();
+        emit_tiles(off, tid < G ? my_count : 0, G, tall_rows, s_scan, n_tiles, tile_map);
+    }
+    __syncthreads();
+    const int idx = blockIdx.x * 1024 + tid;
     if (idx < N) {
         const int e = ids[idx];
-        const int pos = offsets[e] + hist[(size_t)(idx / kDispChunk) * E + e] + inv_perm[idx];
+        const int pos = s_base[e] + inv_perm[idx];
         inv_perm[idx] = pos;
         sorted_token[pos] = idx / k;
-    } else if (idx < N + S * T) {
-        sorted_token[idx] = (idx - N) % T;
     }
+    for (int i = blockIdx.x * 1024 + tid; i < S * T; i += gridDim.x * 1024) sorted_token[N + i] = i % T;
 }
 
 hipError_t launch_dispatch(const moe_config& c, const int* topk_ids, int T, int n_shared_groups, int* offsets,
@@ -341,12 +371,10 @@ hipError_t launch_dispatch(const moe_config& c, const int* topk_ids, int T, int 
         return hipGetLastError();
     }
     const int n_chunks = (N + kDispChunk - 1) / kDispChunk;
+    static_assert(kDispChunk == 1024, "the scatter kernel places one chunk per 1024-thread workgroup");
     hipLaunchKernelGGL(dispatch_rank_kernel, dim3(n_chunks), dim3(256), 0, st, topk_ids, N, c.E, inv_perm, hist);
-    hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(1024), 0, st, hist, n_chunks, T, c.E, S, tall_rows, offsets, n_tiles,
-                       tile_map);
-    const int total = N + S * T;
-    hipLaunchKernelGGL(dispatch_scatter_kernel, dim3((total + 255) / 256), dim3(256), 0, st, topk_ids, T, c.k, c.E, S,
-                       offsets, hist, sorted_token, inv_perm);
+    hipLaunchKernelGGL(dispatch_scatter_kernel, dim3(n_chunks), dim3(1024), 0, st, topk_ids, T, c.k, c.E, S,
+                       small_route_ep(c.E), tall_rows, hist, n_chunks, offsets, n_tiles, tile_map, sorted_token, inv_perm);
     return hipGetLastError();
 }
 
