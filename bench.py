@@ -205,7 +205,10 @@ def measure_compress(name, steps, warmup, with_cpu_baseline):
            "us_per_call": us, "visual_tokens_per_s": N / (us * 1e-6),
            "roofline": {"bound": "hbm", "achieved": nbytes / (us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": nbytes / (us * 1e-6) / 1e9 / PEAK_HBM_GBS, "traffic": None,
-                        "kernel": "compress_prepare_kernel + compress_select_kernel", "algorithmic_bytes": nbytes}}
+                        "kernel": ("compress_prepare_kernel + compress_select_kernel"
+                                   if N < moe.moe_compress_wide_min_tokens(-1)
+                                   else "compress_prepare_kernel + the wide_* chain (14 launches)"),
+                        "algorithmic_bytes": nbytes}}
     if with_cpu_baseline:
         from oracle import compress_oracle as CO
         reps, t0 = 0, time.perf_counter()
@@ -446,6 +449,8 @@ def main():
     if not a.no_also:
         line.setdefault("also", {})["token_compress_P2"] = measure_compress("P2", max(a.steps, 200), a.warmup,
                                                                             not a.no_cpu_baseline)
+        # the long-video size, which takes the compressor's many-workgroup path
+        line["also"]["token_compress_P3"] = measure_compress("P3", max(a.steps, 200), a.warmup, False)
         line["also"]["predictor_features"] = measure_predictor_features(max(a.steps, 200), a.warmup)
         line["also"]["expert_cache"] = measure_expert_cache()
         line["also"]["expert_cache"]["prefetch_pipeline"] = measure_prefetch_pipeline()
