@@ -22,6 +22,9 @@ done
 B="python3 $R/bench.py --config P2 --no-cpu-baseline"
 timeout -s KILL 200 rocprofv3 --kernel-trace --stats -d $O/P2_trace -o t --output-format csv -- $B --steps 200 --warmup 10 > $O/P2_trace.log 2>&1 || exit 6
 echo P2 trace done
+B="python3 $R/bench.py --config P3 --no-cpu-baseline"
+timeout -s KILL 200 rocprofv3 --kernel-trace --stats -d $O/P3_trace -o t --output-format csv -- $B --steps 200 --warmup 10 > $O/P3_trace.log 2>&1 || exit 8
+echo P3 trace done
 B="python3 $R/bench.py --config PF"
 timeout -s KILL 200 rocprofv3 --kernel-trace --stats -d $O/PF_trace -o t --output-format csv -- $B --steps 200 --warmup 10 > $O/PF_trace.log 2>&1 || exit 7
 echo PF trace done

@@ -158,13 +158,15 @@ def regen(raw, out_dir="profiles"):
     for W, cfg, what, calls in (
             ("P2", "P2 --no-cpu-baseline", "token compressor workload P2",
              "50 spin-up + 200 timed calls of moe_token_compress"),
+            ("P3", "P3 --no-cpu-baseline", "token compressor workload P3 (32 768 tokens: the many-workgroup path)",
+             "50 spin-up + 200 timed calls of moe_token_compress"),
             ("PF", "PF", "predictor feature construction",
              "50 spin-up + 200 timed calls each of moe_mean_pool, moe_routing_histogram, moe_lookahead_target, "
              "moe_predictor_forward")):
         d = os.path.join(raw, f"{W}_trace")
         if not os.path.isdir(d):
             continue
-        name = "token_compress_P2.txt" if W == "P2" else "predictor_features_PF.txt"
+        name = {"P2": "token_compress_P2.txt", "P3": "token_compress_P3.txt"}.get(W, "predictor_features_PF.txt")
         with open(os.path.join(out_dir, name), "w") as f:
             f.write(f"# rocprofv3 summary, {what} (bench.py --config {W}), one MI355X, kernels of libvismoe\n\n"
                     "## kernel durations\n"

@@ -157,6 +157,33 @@ def test_benchmark_configs_full_size(gpu, name):
     assert np.array_equal(got, got2) and np.array_equal(ids, ids2) and np.array_equal(w, w2)
 
 
+# (T, E, k): many 1024-assignment chunks, so that every scatter workgroup adds up the chunk x expert table in several
+# batches of loads (E = 512 leaves two thread groups, 16 x 2 chunks per batch), and a skewed id distribution
+@pytest.mark.parametrize("T,E,k", [(40000, 512, 8), (150000, 128, 2), (70001, 8, 3), (9000, 200, 64)])
+def test_dispatch_many_chunks(gpu, T, E, k):
+    torch, moe = gpu
+    _print(f"dispatch case T={T} E={E} k={k}")
+    rng = np.random.default_rng(T + E)
+    # k distinct ids per token, drawn with weights that fall off steeply: a few large groups, many small, some empty
+    w = 1.0 / (1.0 + np.arange(E)) ** 1.5
+    w[rng.permutation(E)[: E // 8]] = 0.0
+    key = rng.random((T, E)) ** (1.0 / np.maximum(w, 1e-12))
+    key[:, w == 0.0] = -1.0
+    ids = np.argsort(-key, axis=1, kind="stable")[:, :k].astype(np.int32)
+    cfg = moe.MoEConfig(H=64, I=64, E=E, k=k, S=0, norm_topk=1, max_tokens=T)
+    ws = moe.alloc_workspace(cfg)
+    d_ids = torch.from_numpy(ids).cuda()
+    off = torch.zeros(E + 1, dtype=torch.int32, device="cuda")
+    st = torch.zeros(T * k, dtype=torch.int32, device="cuda")
+    inv = torch.zeros(T * k, dtype=torch.int32, device="cuda")
+    moe.moe_dispatch(cfg, d_ids, T, off, st, inv, ws)
+    torch.cuda.synchronize()
+    o2, s2, i2 = O.dispatch(ids, E)
+    assert np.array_equal(off.cpu().numpy(), o2)
+    assert np.array_equal(st.cpu().numpy(), s2)
+    assert np.array_equal(inv.cpu().numpy(), i2)
+
+
 def test_edge_cases(gpu):
     torch, moe = gpu
     # all tokens to one expert, every other expert empty: one router row dominates
