@@ -207,7 +207,7 @@ def measure_compress(name, steps, warmup, with_cpu_baseline):
                         "frac": nbytes / (us * 1e-6) / 1e9 / PEAK_HBM_GBS, "traffic": None,
                         "kernel": ("compress_prepare_kernel + compress_select_kernel"
                                    if N < moe.moe_compress_wide_min_tokens(-1)
-                                   else "compress_prepare_kernel + the wide_* chain (14 launches)"),
+                                   else "compress_prepare_kernel + the wide_* chain (11 launches)"),
                         "algorithmic_bytes": nbytes}}
     if with_cpu_baseline:
         from oracle import compress_oracle as CO

@@ -76,7 +76,7 @@ def test_small_cases(env, case):
 
 @pytest.fixture
 def wide_path(env):
-    """Forces the many-workgroup code path for every token count (it is otherwise taken from about 12 K tokens on)."""
+    """Forces the many-workgroup code path for every token count (it is otherwise taken from about 7 K tokens on)."""
     _, moe = env
     before = moe.moe_compress_wide_min_tokens(0)
     yield
