@@ -1,6 +1,7 @@
 // Feature construction of the lookahead predictor (paper Sec. 3.3.1, Eq. 6-7) and its decayed target (Sec. 3.3.2,
 // Eq. 9): mean pooling over the retained tokens, a routing histogram, and the windowed target score.
 #include "common.h"
+#include "topk.h"
 
 namespace vismoe {
 
@@ -182,6 +183,22 @@ __global__ __launch_bounds__(256) void gemv_affine_kernel(const float* __restric
     }
 }
 
+// Maximum / minimum over the wave: inside each 16-lane row by DPP steps, across the four rows through scalar
+// registers. (A butterfly of cross-lane shuffles goes through the LDS crossbar, about a hundred cycles per step:
+// with twelve of them in each of the B rounds this kernel took 10.8 us for B = 20.)
+__device__ __forceinline__ float wave_max_f(float v) {
+    v = row_max(v);
+    const int b = __float_as_int(v);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(b, 0)), r1 = __int_as_float(__builtin_amdgcn_readlane(b, 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(b, 32)), r3 = __int_as_float(__builtin_amdgcn_readlane(b, 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+__device__ __forceinline__ int wave_min_i(int v) {
+    v = row_min(v);
+    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+
 // The B highest entries of y[0..E), descending, ties to the lower index (the ordered prefetch candidates). One wave.
 __global__ __launch_bounds__(kWave) void top_b_kernel(const float* __restrict__ y, int E, int B, int* __restrict__ top) {
     const int lane = threadIdx.x;
@@ -196,12 +213,12 @@ __global__ __launch_bounds__(kWave) void top_b_kernel(const float* __restrict__ 
         float best = -INFINITY;
 #pragma unroll
         for (int j = 0; j < kPer; ++j) best = fmaxf(best, v[j]);
-        for (int o = 32; o > 0; o >>= 1) best = fmaxf(best, __shfl_xor(best, o));
+        best = wave_max_f(best);
         int bi = 0x7fffffff;
 #pragma unroll
         for (int j = kPer - 1; j >= 0; --j)
             if (v[j] == best && lane + kWave * j < E) bi = lane + kWave * j;
-        for (int o = 32; o > 0; o >>= 1) bi = min(bi, __shfl_xor(bi, o));
+        bi = wave_min_i(bi);
 #pragma unroll
         for (int j = 0; j < kPer; ++j)
             if (lane + kWave * j == bi) v[j] = -INFINITY;
