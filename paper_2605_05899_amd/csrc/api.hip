@@ -397,15 +397,15 @@ moe_status moe_layer_forward(const moe_config* cfg, const moe_bf16* x, int32_t T
     if ((s = chk.result()) != MOE_OK) return s;
 
     timer_reset();
-    if (small_route_ok(T, cfg->E, k)) {
-        // small batch (decode): K-sliced logits over many workgroups, a top-k kernel, a single-workgroup dispatch
+    if (sliced_route_ok(T, cfg->E)) {
+        // K-sliced logits over many workgroups, a top-k kernel, then the dispatch (one workgroup for small batches)
         int n_slices = 0;
         timer_mark(0, 0, st);
         VISMOE_TRY(launch_route_partial(*cfg, x, keep_idx, T, w_router, w.partial, &n_slices, st), "route (logits)");
         timer_mark(0, 1, st);
         timer_mark(1, 0, st);
         VISMOE_TRY(launch_route_finish_dispatch(*cfg, w.partial, n_slices, T, S, ids, gw, w.offsets, w.sorted_token,
-                                                w.inv_perm, w.n_tiles, w.tile_map, st), "route (top-k) + dispatch");
+                                                w.inv_perm, w.n_tiles, w.tile_map, w.hist, st), "route (top-k) + dispatch");
         timer_mark(1, 1, st);
     } else {
         timer_mark(0, 0, st);

@@ -46,18 +46,21 @@ static inline int tall_rows_for(long long rows, int G, int H, int I) {
 constexpr int kDispChunk = 1024;
 // Largest T*k handled by the single-workgroup dispatch.
 constexpr int kDispSmallMax = 8192;
-// Small-batch router (few tokens: decode, small or pruned prefill): the contraction is cut into at most kSmallSlices
-// K groups (of four wave slices each) whose partial logits, T x padded E floats per group, go through the workspace.
-constexpr int kSmallLogits = 65536;
+// K-sliced router (decode, small or pruned prefill, mid-size prefill): the contraction is cut into at most
+// kSmallSlices K groups (of four wave slices each) whose partial logits, T x padded E floats per group, go through
+// the workspace. With few token blocks the one-kernel router leaves most CUs idle and every workgroup walks all of K
+// alone (about 20 us whatever the batch); sliced over K the walk is a quarter as long on four times the workgroups.
+constexpr int kSmallLogits = 262144;
 constexpr int kSmallSlices = 4;
-// Expert count padded to a power of two >= 32 (the fragment width) for the small-batch router.
+// Expert count padded to a power of two >= 32 (the fragment width) for the K-sliced router.
 static inline int small_route_ep(int E) {
     int ep = 32;
     while (ep < E) ep <<= 1;
     return ep;
 }
-static inline bool small_route_ok(int T, int E, int k) {
-    return T > 0 && (long long)T * small_route_ep(E) <= kSmallLogits && (long long)T * k <= kDispSmallMax;
+// The K-sliced router is used when its partial logits fit the workspace.
+static inline bool sliced_route_ok(int T, int E) {
+    return T > 0 && (long long)T * small_route_ep(E) <= kSmallLogits;
 }
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -158,7 +161,7 @@ hipError_t launch_route_partial(const moe_config& c, const bf16_t* x, const int*
                                 float* partial, int* n_slices_out, hipStream_t st);
 hipError_t launch_route_finish_dispatch(const moe_config& c, const float* partial, int n_slices, int T, int S,
                                         int* topk_ids, float* topk_w, int* offsets, int* sorted_token, int* inv_perm,
-                                        int* n_tiles, int4* tile_map, hipStream_t st);
+                                        int* n_tiles, int4* tile_map, int* hist, hipStream_t st);
 hipError_t launch_shared_groups(int T, int S, int* offsets, int* sorted_token, hipStream_t st);
 hipError_t launch_grouped_gemm(int mode, bool skinny, const GemmParams& p, int max_rows, hipStream_t st);
 hipError_t launch_slab_report(int E, const int* offsets, const bf16_t* const* slabs, int* missing, hipStream_t st);

@@ -230,23 +230,21 @@ __global__ __launch_bounds__(64) void route_topk_small_kernel(const float* __res
 
 hipError_t launch_route_finish_dispatch(const moe_config& c, const float* partial, int n_slices, int T, int S,
                                         int* topk_ids, float* topk_w, int* offsets, int* sorted_token, int* inv_perm,
-                                        int* n_tiles, int4* tile_map, hipStream_t st) {
+                                        int* n_tiles, int4* tile_map, int* hist, hipStream_t st) {
 #define VISMOE_RFD(EP)                                                                                              \
-    do {                                                                                                            \
-        hipLaunchKernelGGL(route_topk_small_kernel<EP>, dim3((T + 3) / 4), dim3(64), 0, st, partial, n_slices, T, c.k, \
-                           c.E, c.norm_topk, topk_ids, topk_w);                                                     \
-        hipLaunchKernelGGL(dispatch_small_kernel, dim3(1), dim3(1024), 0, st, topk_ids, T, c.k, c.E, S, tall_rows,   \
-                           offsets, sorted_token, inv_perm, n_tiles, tile_map);                                     \
-    } while (0)
+    hipLaunchKernelGGL(route_topk_small_kernel<EP>, dim3((T + 3) / 4), dim3(64), 0, st, partial, n_slices, T, c.k,  \
+                       c.E, c.norm_topk, topk_ids, topk_w)
     const int ep = small_route_ep(c.E);
-    const int tall_rows = tall_rows_for((long long)T * (c.k + S), c.E + S, c.H, c.I);
     if (ep == 32) VISMOE_RFD(32);
     else if (ep == 64) VISMOE_RFD(64);
     else if (ep == 128) VISMOE_RFD(128);
     else if (ep == 256) VISMOE_RFD(256);
     else VISMOE_RFD(512);
 #undef VISMOE_RFD
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // one workgroup when the assignments fit it, the two-kernel dispatch otherwise
+    return launch_dispatch(c, topk_ids, T, S, offsets, sorted_token, inv_perm, n_tiles, tile_map, hist, st);
 }
 
 // ---------------------------------------------------------------- large path
