@@ -41,7 +41,13 @@ __global__ __launch_bounds__(128) void combine_kernel(const bf16_t* __restrict__
             w[i] = topk_w[(size_t)t * k + s0 + i];
         }
 #pragma unroll
-        for (int i = 0; i < N; ++i) v[i] = *reinterpret_cast<const uint4*>(y + (size_t)pos[i] * H + col);
+        // every element of y is read exactly once: loads marked non-temporal (the 268 MB of the video prefill otherwise
+        // push their way through the caches; 55.7 -> 49.3 us on that workload, no change on the small ones)
+        for (int i = 0; i < N; ++i) {
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(y + (size_t)pos[i] * H + col));
+            v[i] = make_uint4(t.x, t.y, t.z, t.w);
+        }
 #pragma unroll
         for (int i = 0; i < N; ++i) fma_piece(v[i], w[i]);
     };
