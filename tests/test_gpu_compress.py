@@ -146,7 +146,7 @@ def test_ties_wide_path(env, wide_path):
     several workgroups, so the rank among equal keys in token order decides."""
     torch, moe = env
     rng = np.random.default_rng(7)
-    N = 3000
+    N = 10000                                  # three workgroups of 4096 tokens on the many-workgroup path
     A = rng.integers(0, 4, size=(1, N)).astype(np.float32)
     R = rng.integers(0, 16, size=(2, N, 2)).astype(np.int32)
     R[:, N // 2:, :] = 3                       # half of the tokens share one expert set: equal scores
