@@ -62,6 +62,7 @@ SMALL = [
     (207, 3000, 12, 128, 4, 8),
     (208, 5000, 5, 512, 2, 8),
     (209, 2049, 2, 200, 1, 64),
+    (210, 20001, 4, 96, 2, 4),          # five workgroups on the many-workgroup path, a ragged last one
 ]
 
 
